@@ -1,0 +1,177 @@
+/* dasgd.h -- C ABI of the DaSGD per-step parameter pipeline for one MI355X (gfx950).
+ *
+ * DaSGD = Local SGD with delayed averaging.  W worker replicas of one model (the paper's M
+ * workers) live in the HBM of one GPU.  Every iteration k each replica takes a local
+ * optimiser step; every tau iterations the replicas' weights are averaged in the
+ * background; d iterations after an average was launched it is folded into every replica's
+ * current weights (paper, Section 3.3.1, Eq. 2):
+ *
+ *     x_{k+1}^(m) = x_k^(m) - eta g(x_k^(m))                                   otherwise
+ *     x_{k+1}^(m) = xi (x_k^(m) - eta g(x_k^(m)))
+ *                   + (1 - xi) (1/M) sum_j [ x_{k-d}^(j) - eta g(x_{k-d}^(j)) ]    if (k+1-d) mod tau == 0
+ *
+ * The averaging (a network all-reduce in the paper) is an on-device W-way mean here, run on a
+ * side stream so that it overlaps the following local steps (paper, Fig. 2 and Fig. 4).
+ *
+ * Conventions
+ *   - All pointers named "device" point to GPU memory owned by the CALLER (allocated e.g. by
+ *     PyTorch); the library allocates no device memory.  All pointer ARRAYS are host memory.
+ *   - Streams are raw hipStream_t handles passed as void*; the caller owns them.
+ *   - Every step call only enqueues work and returns; only dasgd_bind (set-up copies),
+ *     dasgd_profile_read and dasgd_destroy block the host.
+ *   - A context is not thread-safe.  Functions return DASGD_OK or a negative error code and
+ *     leave the context unchanged on error.
+ *   - k denotes the 0-based index of the most recently completed local step.
+ *
+ * Canonical caller loop (one iteration of Eq. 2):
+ *     dasgd_local_step(ctx, g);
+ *     dasgd_query(ctx, &k, &n_pending, &begin_due, &merge_due);
+ *     if (begin_due) dasgd_average_begin(ctx);     // (k+1) mod tau == 0
+ *     if (merge_due) dasgd_merge(ctx);             // an average launched at k-d is pending
+ */
+#ifndef DASGD_H
+#define DASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dasgd_ctx dasgd_ctx;
+
+enum {
+    DASGD_OK     = 0,
+    DASGD_EINVAL = -1,  /* bad argument: W<1, P<1, d<0, tau<1, non-finite or negative lr, momentum
+                           outside [0,1), wd<0, xi outside [0,1], null pointer, sizes that do not add up */
+    DASGD_ESTATE = -2,  /* call not legal in the current state (see each function) */
+    DASGD_ENOMEM = -3,  /* workspace too small / host allocation failed */
+    DASGD_EHIP   = -4   /* a HIP runtime call failed; code via dasgd_last_hip_error */
+};
+
+/* Schedules (dasgd_set_schedule).  All use the same kernels. */
+enum {
+    DASGD_SCHED_OVERLAP = 0, /* default: the W-way mean runs on the side stream, event-ordered
+                                (the paper's point: averaging hidden behind d local steps) */
+    DASGD_SCHED_SERIAL  = 1, /* everything on the main stream in program order (no overlap) */
+    DASGD_SCHED_NO_AVERAGE_TIMING_ONLY = 2 /* timing floor: no snapshot and no mean are run, the
+                                merge reads whatever the slot holds.  RESULTS ARE MEANINGLESS. */
+};
+
+/* Kernels for dasgd_profile_read. */
+enum {
+    DASGD_K_LOCAL_STEP      = 0, /* local step without snapshot store */
+    DASGD_K_LOCAL_STEP_SNAP = 1, /* local step that also stores the snapshot */
+    DASGD_K_MEAN            = 2, /* W-way replica mean */
+    DASGD_K_MERGE           = 3, /* delayed merge */
+    DASGD_K_COUNT           = 4
+};
+
+/* Create a context for W replicas of P fp32 parameters each.
+ *   d    delay in local steps between launching an average and merging it (d >= 0; the paper
+ *        analyses d < tau, Section 4.3; any d is accepted: floor(d/tau)+1 averages in flight)
+ *   tau  local steps between two averages (tau >= 1)
+ *   lr, momentum, wd   learning rate eta (>= 0, finite), heavy-ball momentum in [0,1), coupled
+ *        L2 weight decay (>= 0)  (Section 4.1 gives the constants 0.9 and 0.01)
+ * xi, the local update proportion of Eq. 2, starts at 0.25 (the only value the paper prints,
+ * Section 4.3); change it with dasgd_set_xi.  Host-only: needs no GPU.
+ * Returns NULL on invalid arguments or allocation failure. */
+dasgd_ctx *dasgd_create(int W, int64_t P, int d, int tau, float lr, float momentum, float wd);
+
+/* Set xi in [0,1] (Eq. 2: weight of the local value at a merge).  Takes effect from the next merge. */
+int dasgd_set_xi(dasgd_ctx *ctx, float xi);
+
+/* Set the learning rate (caller-side schedules; the paper's runs use a one-cycle policy,
+ * Section 4.1).  Takes effect from the next local step. */
+int dasgd_set_lr(dasgd_ctx *ctx, float lr);
+
+/* Choose the schedule (DASGD_SCHED_*).  Only legal while no average is pending. */
+int dasgd_set_schedule(dasgd_ctx *ctx, int schedule);
+
+/* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
+ * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots
+ * (floor(d/tau)+1 slots of W x P' floats) and the averages (same number of slots of P' floats),
+ * where P' pads every tensor to a multiple of 64 elements.  Returns 0 on invalid arguments. */
+size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
+
+/* Bind the replicas' storage.
+ *   numel      [n_tensors] host array, sum == P
+ *   x, v       [W * n_tensors] host arrays of device pointers, replica-major (entry j*n_tensors+t is
+ *              tensor t of replica j); each tensor contiguous fp32, at least 4-byte aligned
+ *              (16-byte alignment selects the 128-bit path).  x: weights, updated in place.
+ *              v: momentum buffers, updated in place; the caller zero-initialises them (v_0 = 0).
+ *              All replicas are expected to start from the same weights (paper, Lemma 1); the
+ *              library does not check it.
+ *   workspace  device memory, 256-byte aligned, at least dasgd_workspace_bytes(...) bytes; its
+ *              contents belong to the library until dasgd_destroy
+ *   main_stream, side_stream   hipStream_t handles; local step and merge run on main_stream,
+ *              the W-way mean on side_stream.  Must be different streams of equal priority.
+ * Copies the tables to the device and clears snapshots/averages (blocks until done).
+ * Errors: EINVAL, ENOMEM (workspace too small), ESTATE (already bound), EHIP. */
+int dasgd_bind(dasgd_ctx *ctx, int n_tensors, const int64_t *numel,
+               float *const *x, float *const *v,
+               void *workspace, size_t workspace_bytes,
+               void *main_stream, void *side_stream);
+
+/* Bind shapes only: every later step call runs the host-side state machine (step counter,
+ * pending-average ring, due/overdue checks, error codes) and launches NOTHING on any device.
+ * For testing schedules and error handling on machines without a GPU; computes nothing. */
+int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
+
+/* Local step k -> k+1 on every replica (Eq. 2, first branch, with the optimiser of Section 4.1):
+ *     g' = g + wd x ;  v <- momentum v + g' ;  x <- x - lr v
+ * one fused kernel over all replicas and tensors on main_stream.  When (k+1) mod tau == 0 the
+ * same kernel also stores the new weights into a snapshot slot for the average that
+ * dasgd_average_begin will launch.
+ *   g   [W * n_tensors] host array of device pointers (same order and shapes as x), read only;
+ *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
+ *       pointers of the previous call (the table is re-uploaded only when it changes).
+ * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
+int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
+
+/* Launch the average of the weights as they were right after the latest local step (Eq. 2's
+ * summand x - eta g; matrix form (X - eta G) J in the appendix): A = (1/W) sum_j snapshot_j, on
+ * side_stream after main_stream's local step, occupying a ring slot until merged.
+ * ESTATE: not due (legal exactly once after a local step k with (k+1) mod tau == 0). */
+int dasgd_average_begin(dasgd_ctx *ctx);
+
+/* Fold the oldest pending average into every replica (Eq. 2, second branch):
+ *     x_j <- xi x_j + (1 - xi) A        computed as x_j + (1 - xi)(A - x_j)
+ * on main_stream, after a device-side wait for that average; frees its slot.
+ * ESTATE: no pending average, or the oldest one was not launched at step k - d. */
+int dasgd_merge(dasgd_ctx *ctx);
+
+/* Report the state: k (index of the last completed local step, -1 before the first), number of
+ * pending averages, and whether dasgd_average_begin / dasgd_merge are due now.  Any output
+ * pointer may be NULL. */
+int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begin_due, int *merge_due);
+
+/* Layout of the library-owned buffers inside the workspace, for inspection by tests and tools:
+ * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
+ * *P_padded = elements per row.  ESTATE if not bound. */
+int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
+
+/* Locate pending average number `which` (0 = oldest): its launch step and the byte offset of its
+ * P_padded floats from the start of the workspace.  The data is complete once side_stream (or
+ * main_stream in the serial schedule) has drained.  EINVAL if which is out of range. */
+int dasgd_pending_average(const dasgd_ctx *ctx, int which, int64_t *launch_step, size_t *byte_offset);
+
+/* Per-kernel timing.  enable != 0: bracket every kernel launch with timing events on its own
+ * stream (at most max_records launches are recorded; later ones run untimed).  enable == 0: stop. */
+int dasgd_profile(dasgd_ctx *ctx, int enable, int max_records);
+
+/* Wait for both streams, then return the summed duration and the number of recorded launches of
+ * kernel `kernel` (DASGD_K_*) since profiling was enabled or last read, and reset them. */
+int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *launches);
+
+/* HIP error code of the most recent DASGD_EHIP (0 if none). */
+int dasgd_last_hip_error(const dasgd_ctx *ctx);
+
+/* Wait for both streams, drop pending averages, release events and host state.  NULL is a no-op. */
+void dasgd_destroy(dasgd_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASGD_H */

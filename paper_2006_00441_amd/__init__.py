@@ -1,0 +1,14 @@
+"""DaSGD (Local SGD with delayed averaging) parameter pipeline for one MI355X.
+
+The work is done by hand-written HIP kernels behind a C ABI (include/dasgd.h, built into
+libdasgd.so); this package is the ctypes binding.  There is no CPU fallback: importing works
+anywhere (the context's host-side state machine needs no GPU), but binding device memory and
+stepping need the built library and a gfx950 GPU, and fail loudly otherwise.
+"""
+from .binding import (DaSGD, DasgdError, lib, library_path, DASGD_OK, DASGD_EINVAL, DASGD_ESTATE,
+                      DASGD_ENOMEM, DASGD_EHIP, SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY,
+                      K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, KERNEL_NAMES, EXPORTS)
+
+__all__ = ["DaSGD", "DasgdError", "lib", "library_path", "DASGD_OK", "DASGD_EINVAL", "DASGD_ESTATE",
+           "DASGD_ENOMEM", "DASGD_EHIP", "SCHED_OVERLAP", "SCHED_SERIAL", "SCHED_NO_AVERAGE_TIMING_ONLY",
+           "K_LOCAL_STEP", "K_LOCAL_STEP_SNAP", "K_MEAN", "K_MERGE", "KERNEL_NAMES", "EXPORTS"]

@@ -1,0 +1,243 @@
+"""ctypes binding of include/dasgd.h: argument marshalling only.
+
+`lib()` returns the loaded shared library with typed signatures; `DaSGD` wraps one context and
+turns negative return codes into `DasgdError`.  Every method maps one-to-one onto the C call of
+the same name (dasgd_local_step -> DaSGD.local_step, ...).  The only convenience is
+`bind_tensors`, which takes torch tensors, collects their data pointers and allocates the
+workspace with torch (PyTorch supplies device memory and streams; it computes nothing here).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+from . import build as _build
+
+DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
+SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY = 0, 1, 2
+K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE = 0, 1, 2, 3
+KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
+                K_MEAN: "mean", K_MERGE: "merge"}
+_ERR = {DASGD_EINVAL: "DASGD_EINVAL (bad argument)", DASGD_ESTATE: "DASGD_ESTATE (call illegal in this state)",
+        DASGD_ENOMEM: "DASGD_ENOMEM (workspace too small)", DASGD_EHIP: "DASGD_EHIP (HIP call failed)"}
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+_pp = ctypes.POINTER(ctypes.c_void_p)
+_pi64 = ctypes.POINTER(ctypes.c_int64)
+_pint = ctypes.POINTER(ctypes.c_int)
+
+# name -> (restype, argtypes): every symbol include/dasgd.h declares
+EXPORTS = {
+    "dasgd_create": (_vp, [ctypes.c_int, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_float]),
+    "dasgd_set_xi": (ctypes.c_int, [_vp, ctypes.c_float]),
+    "dasgd_set_lr": (ctypes.c_int, [_vp, ctypes.c_float]),
+    "dasgd_set_schedule": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "dasgd_workspace_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int, _pi64]),
+    "dasgd_bind": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, _pp, _pp, _vp, ctypes.c_size_t, _vp, _vp]),
+    "dasgd_bind_dry_run": (ctypes.c_int, [_vp, ctypes.c_int, _pi64]),
+    "dasgd_local_step": (ctypes.c_int, [_vp, _pp]),
+    "dasgd_average_begin": (ctypes.c_int, [_vp]),
+    "dasgd_merge": (ctypes.c_int, [_vp]),
+    "dasgd_query": (ctypes.c_int, [_vp, _pi64, _pint, _pint, _pint]),
+    "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64]),
+    "dasgd_pending_average": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, ctypes.POINTER(ctypes.c_size_t)]),
+    "dasgd_profile": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
+    "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64]),
+    "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
+    "dasgd_destroy": (None, [_vp]),
+}
+
+_LIB: Optional[ctypes.CDLL] = None
+
+
+class DasgdError(RuntimeError):
+    def __init__(self, call: str, code: int, hip: int = 0):
+        self.call, self.code, self.hip = call, code, hip
+        msg = f"{call} failed: {_ERR.get(code, code)}"
+        if code == DASGD_EHIP:
+            msg += f" [hipError {hip}]"
+        super().__init__(msg)
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib() -> ctypes.CDLL:
+    """Load libdasgd.so (what is built in-tree; built here only if nothing is)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        try:
+            _build.build()
+        except Exception as e:  # no silent fallback: there is no other implementation
+            raise RuntimeError(f"libdasgd.so is not built and could not be built here ({e}); "
+                               "run `python -c 'import __graft_entry__ as g; g.build()'`") from e
+    L = ctypes.CDLL(path)
+    for name, (res, args) in EXPORTS.items():
+        f = getattr(L, name)
+        f.restype = res
+        f.argtypes = args
+    _LIB = L
+    return L
+
+
+def _ptr_array(ptrs: Sequence[int]):
+    arr = (ctypes.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
+    return arr
+
+
+class DaSGD:
+    """One DaSGD context: W replicas of P fp32 parameters; see include/dasgd.h for semantics."""
+
+    def __init__(self, W: int, P: int, d: int, tau: int, lr: float, momentum: float, wd: float,
+                 xi: Optional[float] = None):
+        self._lib = lib()
+        self._h = self._lib.dasgd_create(int(W), int(P), int(d), int(tau), float(lr), float(momentum), float(wd))
+        if not self._h:
+            raise DasgdError("dasgd_create", DASGD_EINVAL)
+        self.W, self.P, self.d, self.tau = int(W), int(P), int(d), int(tau)
+        self.n_tensors = 0
+        self._keep = []            # torch objects whose memory the library points into
+        self._g_arr = None
+        if xi is not None:
+            self.set_xi(xi)
+
+    # -- helpers -------------------------------------------------------------------------------
+    def _check(self, call: str, rc: int) -> int:
+        if rc < 0:
+            raise DasgdError(call, rc, self._lib.dasgd_last_hip_error(self._h))
+        return rc
+
+    # -- one method per C call -------------------------------------------------------------------
+    def set_xi(self, xi: float) -> None:
+        self._check("dasgd_set_xi", self._lib.dasgd_set_xi(self._h, float(xi)))
+
+    def set_lr(self, lr: float) -> None:
+        self._check("dasgd_set_lr", self._lib.dasgd_set_lr(self._h, float(lr)))
+
+    def set_schedule(self, schedule: int) -> None:
+        self._check("dasgd_set_schedule", self._lib.dasgd_set_schedule(self._h, int(schedule)))
+
+    def workspace_bytes(self, numel: Sequence[int]) -> int:
+        arr = (ctypes.c_int64 * len(numel))(*[int(n) for n in numel])
+        return int(self._lib.dasgd_workspace_bytes(self._h, len(numel), arr))
+
+    def bind(self, numel: Sequence[int], x_ptrs: Sequence[int], v_ptrs: Sequence[int],
+             workspace_ptr: int, workspace_bytes: int, main_stream: int, side_stream: int) -> None:
+        n = len(numel)
+        arr = (ctypes.c_int64 * n)(*[int(z) for z in numel])
+        if len(x_ptrs) != self.W * n or len(v_ptrs) != self.W * n:
+            raise DasgdError("dasgd_bind", DASGD_EINVAL)
+        self._check("dasgd_bind", self._lib.dasgd_bind(self._h, n, arr, _ptr_array(x_ptrs), _ptr_array(v_ptrs),
+                                                       ctypes.c_void_p(int(workspace_ptr)), int(workspace_bytes),
+                                                       ctypes.c_void_p(int(main_stream)), ctypes.c_void_p(int(side_stream))))
+        self.n_tensors = n
+
+    def bind_dry_run(self, numel: Sequence[int]) -> None:
+        n = len(numel)
+        arr = (ctypes.c_int64 * n)(*[int(z) for z in numel])
+        self._check("dasgd_bind_dry_run", self._lib.dasgd_bind_dry_run(self._h, n, arr))
+        self.n_tensors = n
+
+    def local_step(self, g_ptrs: Optional[Sequence[int]] = None) -> None:
+        """g_ptrs: W*n_tensors device pointers (replica-major) or None to re-use the last table."""
+        if g_ptrs is None:
+            arr = None
+        else:
+            if len(g_ptrs) != self.W * self.n_tensors:
+                raise DasgdError("dasgd_local_step", DASGD_EINVAL)
+            arr = _ptr_array(g_ptrs)
+        self._check("dasgd_local_step", self._lib.dasgd_local_step(self._h, arr))
+
+    def average_begin(self) -> None:
+        self._check("dasgd_average_begin", self._lib.dasgd_average_begin(self._h))
+
+    def merge(self) -> None:
+        self._check("dasgd_merge", self._lib.dasgd_merge(self._h))
+
+    def query(self) -> Tuple[int, int, bool, bool]:
+        """(k, n_pending, begin_due, merge_due)"""
+        k = ctypes.c_int64(); n = ctypes.c_int(); b = ctypes.c_int(); m = ctypes.c_int()
+        self._check("dasgd_query", self._lib.dasgd_query(self._h, ctypes.byref(k), ctypes.byref(n),
+                                                         ctypes.byref(b), ctypes.byref(m)))
+        return int(k.value), int(n.value), bool(b.value), bool(m.value)
+
+    def layout(self) -> Tuple[List[int], int]:
+        """(flat offset of every tensor in a snapshot row / average, padded row length)"""
+        off = (ctypes.c_int64 * max(self.n_tensors, 1))()
+        pp = ctypes.c_int64()
+        self._check("dasgd_layout", self._lib.dasgd_layout(self._h, off, ctypes.byref(pp)))
+        return [int(o) for o in off[: self.n_tensors]], int(pp.value)
+
+    def pending_average(self, which: int = 0) -> Tuple[int, int]:
+        """(launch step, byte offset into the workspace) of pending average `which` (0 = oldest)"""
+        ls = ctypes.c_int64(); bo = ctypes.c_size_t()
+        self._check("dasgd_pending_average",
+                    self._lib.dasgd_pending_average(self._h, int(which), ctypes.byref(ls), ctypes.byref(bo)))
+        return int(ls.value), int(bo.value)
+
+    def profile(self, enable: bool, max_records: int = 4096) -> None:
+        self._check("dasgd_profile", self._lib.dasgd_profile(self._h, 1 if enable else 0, int(max_records)))
+
+    def profile_read(self, kernel: int) -> Tuple[float, int]:
+        """(total milliseconds, launches) of one kernel since enabled / last read; blocks."""
+        ms = ctypes.c_double(); n = ctypes.c_int64()
+        self._check("dasgd_profile_read", self._lib.dasgd_profile_read(self._h, int(kernel), ctypes.byref(ms), ctypes.byref(n)))
+        return float(ms.value), int(n.value)
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None):
+            self._lib.dasgd_destroy(self._h)
+            self._h = None
+            self._keep = []
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # -- the canonical iteration (the caller loop of the header, for convenience) ------------------
+    def step(self, g_ptrs: Optional[Sequence[int]] = None) -> Tuple[bool, bool]:
+        """local_step, then average_begin / merge when due.  Returns (began, merged)."""
+        self.local_step(g_ptrs)
+        _, _, b, _ = self.query()
+        if b:
+            self.average_begin()
+        _, _, _, m = self.query()
+        if m:
+            self.merge()
+        return b, m
+
+    # -- torch marshalling -------------------------------------------------------------------------
+    def bind_tensors(self, x: Sequence[Sequence["torch.Tensor"]], v: Sequence[Sequence["torch.Tensor"]],
+                     main_stream: "torch.cuda.Stream", side_stream: "torch.cuda.Stream") -> "torch.Tensor":
+        """x[j][t], v[j][t]: fp32 contiguous device tensors of replica j.  Allocates the workspace
+        with torch and returns it (a uint8 tensor the caller may inspect but must not free)."""
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("dasgd: no GPU visible; there is no CPU implementation of this path")
+        assert len(x) == self.W and len(v) == self.W
+        numel = [int(t.numel()) for t in x[0]]
+        for rows in (x, v):
+            for rep in rows:
+                assert [int(t.numel()) for t in rep] == numel
+                for t in rep:
+                    assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+        nbytes = self.workspace_bytes(numel)
+        if nbytes == 0:
+            raise DasgdError("dasgd_workspace_bytes", DASGD_EINVAL)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=x[0][0].device)
+        self.bind(numel, [t.data_ptr() for rep in x for t in rep], [t.data_ptr() for rep in v for t in rep],
+                  ws.data_ptr(), nbytes, main_stream.cuda_stream, side_stream.cuda_stream)
+        self._keep = [x, v, ws, main_stream, side_stream]
+        return ws
+
+    @staticmethod
+    def grad_pointers(g: Sequence[Sequence["torch.Tensor"]]) -> List[int]:
+        return [t.data_ptr() for rep in g for t in rep]

@@ -1,0 +1,509 @@
+// Host side of the DaSGD parameter pipeline: the C ABI declared in include/dasgd.h, the
+// pending-average ring, and the stream/event schedule that lets the W-way mean run behind the
+// following local steps (paper, Section 3 and Fig. 2: a worker hands its weights to the averaging
+// and immediately continues; the result is applied d local steps later).
+#include "../../include/dasgd.h"
+#include "kernels.hpp"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <vector>
+
+using namespace dasgd;
+
+namespace {
+
+constexpr int kGTables = 4;         // device copies of the gradient pointer table, used in rotation
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+struct Pending {
+    int64_t launch_step;
+    int slot;
+};
+
+struct ProfRec {
+    int kernel;
+    hipEvent_t start, stop;
+};
+
+struct Layout {                     // byte offsets into the workspace
+    size_t chunks, xp, vp, gp[kGTables], S, A, total;
+    int64_t P_pad, n_chunks;
+    std::vector<int64_t> foff;
+};
+
+}  // namespace
+
+struct dasgd_ctx {
+    // problem
+    int W = 0, d = 0, tau = 1;
+    int64_t P = 0;
+    float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
+    int schedule = DASGD_SCHED_OVERLAP;
+    int slots = 1;
+    // binding
+    bool bound = false, dry = false;
+    int n_tensors = 0;
+    std::vector<int64_t> numel;
+    Layout lay;
+    char *ws = nullptr;
+    hipStream_t main_s = nullptr, side_s = nullptr;
+    // gradient pointer tables
+    std::vector<const float *> g_cached;
+    int g_cur = -1;
+    void *g_pinned = nullptr;       // kGTables host staging tables (pinned)
+    hipEvent_t g_ev[kGTables] = {};
+    bool g_ev_live[kGTables] = {};
+    // schedule state
+    int64_t n_done = 0;             // completed local steps; k = n_done - 1
+    int64_t n_launched = 0;         // averages launched so far
+    bool begun_for_k = false;       // dasgd_average_begin already issued for the current k
+    bool snap_valid = false;        // the latest local step stored a snapshot
+    int snap_slot = 0;
+    std::deque<Pending> pending;
+    std::vector<hipEvent_t> snap_done, avg_done;
+    // profiling
+    bool prof = false;
+    int prof_max = 0;
+    std::vector<ProfRec> prof_recs;
+    std::vector<ProfRec> prof_pool;
+    int last_hip = 0;
+};
+
+namespace {
+
+#define HIPCHK(ctx, expr)                                   \
+    do {                                                    \
+        hipError_t e_ = (expr);                             \
+        if (e_ != hipSuccess) {                             \
+            (ctx)->last_hip = (int)e_;                      \
+            return DASGD_EHIP;                              \
+        }                                                   \
+    } while (0)
+
+bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
+{
+    if (!c || n_tensors < 1 || !numel) return false;
+    int64_t sum = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (numel[t] < 1) return false;
+        sum += numel[t];
+    }
+    return sum == c->P;
+}
+
+Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
+{
+    Layout L;
+    L.foff.resize(n_tensors);
+    int64_t f = 0, nch = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        L.foff[t] = f;
+        f += (numel[t] + kPad - 1) / kPad * kPad;
+        nch += (numel[t] + kChunk - 1) / kChunk;
+    }
+    L.P_pad = f;
+    L.n_chunks = nch;
+    const size_t tbl = sizeof(void *) * (size_t)c->W * (size_t)n_tensors;
+    size_t o = 0;
+    L.chunks = o; o += align_up(sizeof(Chunk) * (size_t)nch);
+    L.xp = o;     o += align_up(tbl);
+    L.vp = o;     o += align_up(tbl);
+    for (int b = 0; b < kGTables; ++b) { L.gp[b] = o; o += align_up(tbl); }
+    L.S = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)c->W * (size_t)L.P_pad);
+    L.A = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)L.P_pad);
+    L.total = o;
+    return L;
+}
+
+inline float *snap_ptr(const dasgd_ctx *c, int slot)
+{
+    return reinterpret_cast<float *>(c->ws + c->lay.S) + (size_t)slot * (size_t)c->W * (size_t)c->lay.P_pad;
+}
+inline float *avg_ptr(const dasgd_ctx *c, int slot)
+{
+    return reinterpret_cast<float *>(c->ws + c->lay.A) + (size_t)slot * (size_t)c->lay.P_pad;
+}
+
+inline bool begin_due(const dasgd_ctx *c)
+{
+    return c->n_done > 0 && (c->n_done % c->tau) == 0 && !c->begun_for_k;     // (k+1) mod tau == 0
+}
+inline bool merge_due(const dasgd_ctx *c)
+{
+    return !c->pending.empty() && c->pending.front().launch_step == (c->n_done - 1) - c->d;
+}
+
+// Timing brackets for one launch (no-ops unless profiling).
+int prof_open(dasgd_ctx *c, int kernel, hipStream_t s, int *rec_index)
+{
+    *rec_index = -1;
+    if (!c->prof || (int)c->prof_recs.size() >= c->prof_max) return DASGD_OK;
+    ProfRec r;
+    if (!c->prof_pool.empty()) {
+        r = c->prof_pool.back();
+        c->prof_pool.pop_back();
+    } else {
+        HIPCHK(c, hipEventCreate(&r.start));
+        HIPCHK(c, hipEventCreate(&r.stop));
+    }
+    r.kernel = kernel;
+    HIPCHK(c, hipEventRecord(r.start, s));
+    c->prof_recs.push_back(r);
+    *rec_index = (int)c->prof_recs.size() - 1;
+    return DASGD_OK;
+}
+int prof_close(dasgd_ctx *c, hipStream_t s, int rec_index)
+{
+    if (rec_index < 0) return DASGD_OK;
+    HIPCHK(c, hipEventRecord(c->prof_recs[rec_index].stop, s));
+    return DASGD_OK;
+}
+
+int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A)
+{
+    const int64_t n4 = c->lay.P_pad / 4;
+    const v4f *S4 = reinterpret_cast<const v4f *>(S);
+    v4f *A4 = reinterpret_cast<v4f *>(A);
+    const float inv_w = 1.0f / (float)c->W;
+    auto grid = [&](int U) { return dim3((unsigned)((n4 + (int64_t)kThreads * U - 1) / ((int64_t)kThreads * U))); };
+    switch (c->W) {
+    case 1:  hipLaunchKernelGGL((k_mean<1, 4, true>),  grid(4), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 2:  hipLaunchKernelGGL((k_mean<2, 4, true>),  grid(4), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 4:  hipLaunchKernelGGL((k_mean<4, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 8:  hipLaunchKernelGGL((k_mean<8, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 16: hipLaunchKernelGGL((k_mean<16, 1, true>), grid(1), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    default: hipLaunchKernelGGL((k_mean<0, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    }
+    HIPCHK(c, hipGetLastError());
+    return DASGD_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+dasgd_ctx *dasgd_create(int W, int64_t P, int d, int tau, float lr, float momentum, float wd)
+{
+    if (W < 1 || W > 65535 || P < 1 || d < 0 || tau < 1) return nullptr;
+    if (!std::isfinite(lr) || lr < 0.f) return nullptr;
+    if (!(momentum >= 0.f && momentum < 1.f)) return nullptr;
+    if (!std::isfinite(wd) || wd < 0.f) return nullptr;
+    dasgd_ctx *c = new (std::nothrow) dasgd_ctx();
+    if (!c) return nullptr;
+    c->W = W; c->P = P; c->d = d; c->tau = tau;
+    c->lr = lr; c->momentum = momentum; c->wd = wd;
+    c->slots = d / tau + 1;
+    return c;
+}
+
+int dasgd_set_xi(dasgd_ctx *c, float xi)
+{
+    if (!c || !(xi >= 0.f && xi <= 1.f)) return DASGD_EINVAL;
+    c->xi = xi;
+    return DASGD_OK;
+}
+
+int dasgd_set_lr(dasgd_ctx *c, float lr)
+{
+    if (!c || !std::isfinite(lr) || lr < 0.f) return DASGD_EINVAL;
+    c->lr = lr;
+    return DASGD_OK;
+}
+
+int dasgd_set_schedule(dasgd_ctx *c, int schedule)
+{
+    if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) return DASGD_EINVAL;
+    if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
+    c->schedule = schedule;
+    return DASGD_OK;
+}
+
+size_t dasgd_workspace_bytes(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
+{
+    if (!shapes_ok(c, n_tensors, numel)) return 0;
+    return make_layout(c, n_tensors, numel).total;
+}
+
+static int bind_common(dasgd_ctx *c, int n_tensors, const int64_t *numel)
+{
+    if (!shapes_ok(c, n_tensors, numel)) return DASGD_EINVAL;
+    if (c->bound) return DASGD_ESTATE;
+    return DASGD_OK;
+}
+
+int dasgd_bind_dry_run(dasgd_ctx *c, int n_tensors, const int64_t *numel)
+{
+    int rc = bind_common(c, n_tensors, numel);
+    if (rc != DASGD_OK) return rc;
+    c->n_tensors = n_tensors;
+    c->numel.assign(numel, numel + n_tensors);
+    c->lay = make_layout(c, n_tensors, numel);
+    c->dry = true;
+    c->bound = true;
+    return DASGD_OK;
+}
+
+int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *x, float *const *v,
+               void *workspace, size_t workspace_bytes, void *main_stream, void *side_stream)
+{
+    int rc = bind_common(c, n_tensors, numel);
+    if (rc != DASGD_OK) return rc;
+    if (!x || !v || !workspace) return DASGD_EINVAL;
+    if (main_stream == side_stream) return DASGD_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return DASGD_EINVAL;
+    const size_t rows = (size_t)c->W * (size_t)n_tensors;
+    for (size_t r = 0; r < rows; ++r) {
+        if (!x[r] || !v[r]) return DASGD_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(x[r]) | reinterpret_cast<uintptr_t>(v[r])) & 3u) return DASGD_EINVAL;
+    }
+    Layout L = make_layout(c, n_tensors, numel);
+    if (workspace_bytes < L.total) return DASGD_ENOMEM;
+
+    // chunk table
+    std::vector<Chunk> chunks;
+    chunks.reserve((size_t)L.n_chunks);
+    for (int t = 0; t < n_tensors; ++t)
+        for (int64_t off = 0; off < numel[t]; off += kChunk) {
+            Chunk ch;
+            ch.off = off;
+            ch.foff = L.foff[t] + off;
+            ch.tensor = t;
+            ch.len = (int32_t)((numel[t] - off) < kChunk ? (numel[t] - off) : kChunk);
+            chunks.push_back(ch);
+        }
+
+    c->n_tensors = n_tensors;
+    c->numel.assign(numel, numel + n_tensors);
+    c->lay = L;
+    c->ws = static_cast<char *>(workspace);
+    c->main_s = static_cast<hipStream_t>(main_stream);
+    c->side_s = static_cast<hipStream_t>(side_stream);
+
+    HIPCHK(c, hipMemcpyAsync(c->ws + L.chunks, chunks.data(), sizeof(Chunk) * chunks.size(), hipMemcpyHostToDevice, c->main_s));
+    HIPCHK(c, hipMemcpyAsync(c->ws + L.xp, x, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
+    HIPCHK(c, hipMemcpyAsync(c->ws + L.vp, v, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
+    // snapshots and averages start at zero (padding elements are averaged too and must stay finite)
+    {
+        const int64_t n4 = (int64_t)((L.total - L.S) / 16);
+        const int64_t want = (n4 + kThreads - 1) / kThreads;
+        const unsigned blocks = (unsigned)(want < 8192 ? (want < 1 ? 1 : want) : 8192);
+        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(kThreads), 0, c->main_s,
+                           reinterpret_cast<v4f *>(c->ws + L.S), n4);
+        HIPCHK(c, hipGetLastError());
+    }
+    HIPCHK(c, hipStreamSynchronize(c->main_s));
+
+    HIPCHK(c, hipHostMalloc(&c->g_pinned, sizeof(void *) * rows * kGTables, hipHostMallocDefault));
+    for (int b = 0; b < kGTables; ++b) HIPCHK(c, hipEventCreateWithFlags(&c->g_ev[b], hipEventDisableTiming));
+    c->snap_done.resize(c->slots);
+    c->avg_done.resize(c->slots);
+    for (int s = 0; s < c->slots; ++s) {
+        HIPCHK(c, hipEventCreateWithFlags(&c->snap_done[s], hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&c->avg_done[s], hipEventDisableTiming));
+    }
+    c->dry = false;
+    c->bound = true;
+    return DASGD_OK;
+}
+
+int dasgd_local_step(dasgd_ctx *c, const float *const *g)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->bound) return DASGD_ESTATE;
+    if (begin_due(c) || merge_due(c)) return DASGD_ESTATE;          // unfinished business of step k
+    const bool snap = ((c->n_done + 1) % c->tau) == 0 && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
+    const bool snap_step = ((c->n_done + 1) % c->tau) == 0;
+    if (snap_step && (int)c->pending.size() >= c->slots) return DASGD_ESTATE;
+    const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
+
+    if (!c->dry) {
+        if (!g && c->g_cur < 0) return DASGD_EINVAL;
+        if (g) {
+            for (size_t r = 0; r < rows; ++r)
+                if (!g[r] || (reinterpret_cast<uintptr_t>(g[r]) & 3u)) return DASGD_EINVAL;
+            const bool changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
+            if (changed) {
+                // retire the table in use (all kernels reading it are already enqueued), take the next
+                if (c->g_cur >= 0) {
+                    HIPCHK(c, hipEventRecord(c->g_ev[c->g_cur], c->main_s));
+                    c->g_ev_live[c->g_cur] = true;
+                }
+                const int b = (c->g_cur + 1) % kGTables;
+                if (c->g_ev_live[b]) {
+                    HIPCHK(c, hipEventSynchronize(c->g_ev[b]));      // its last reader ran kGTables-1 changes ago
+                    c->g_ev_live[b] = false;
+                }
+                void *stage = static_cast<char *>(c->g_pinned) + sizeof(void *) * rows * (size_t)b;
+                std::memcpy(stage, g, sizeof(void *) * rows);
+                HIPCHK(c, hipMemcpyAsync(c->ws + c->lay.gp[b], stage, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
+                c->g_cached.assign(g, g + rows);
+                c->g_cur = b;
+            }
+        }
+        const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
+        float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
+        float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
+        const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
+        const dim3 grid((unsigned)c->lay.n_chunks, (unsigned)c->W);
+        const int slot = (int)(c->n_launched % c->slots);
+        int rec;
+        int rc = prof_open(c, snap ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP, c->main_s, &rec);
+        if (rc != DASGD_OK) return rc;
+        if (snap)
+            hipLaunchKernelGGL((k_local_step<true, true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp,
+                               snap_ptr(c, slot), c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+        else
+            hipLaunchKernelGGL((k_local_step<false, true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp,
+                               (float *)nullptr, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+        HIPCHK(c, hipGetLastError());
+        rc = prof_close(c, c->main_s, rec);
+        if (rc != DASGD_OK) return rc;
+    }
+    c->n_done += 1;
+    c->begun_for_k = false;
+    c->snap_valid = snap_step;
+    c->snap_slot = (int)(c->n_launched % c->slots);
+    return DASGD_OK;
+}
+
+int dasgd_average_begin(dasgd_ctx *c)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->bound || !begin_due(c) || !c->snap_valid) return DASGD_ESTATE;
+    if ((int)c->pending.size() >= c->slots) return DASGD_ESTATE;
+    const int slot = c->snap_slot;
+    if (!c->dry && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) {
+        hipStream_t s = c->main_s;
+        if (c->schedule == DASGD_SCHED_OVERLAP) {
+            HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
+            HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
+            s = c->side_s;
+        }
+        int rec;
+        int rc = prof_open(c, DASGD_K_MEAN, s, &rec);
+        if (rc != DASGD_OK) return rc;
+        rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot));
+        if (rc != DASGD_OK) return rc;
+        rc = prof_close(c, s, rec);
+        if (rc != DASGD_OK) return rc;
+        if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
+    }
+    c->pending.push_back(Pending{c->n_done - 1, slot});
+    c->n_launched += 1;
+    c->begun_for_k = true;
+    return DASGD_OK;
+}
+
+int dasgd_merge(dasgd_ctx *c)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->bound || !merge_due(c)) return DASGD_ESTATE;
+    const int slot = c->pending.front().slot;
+    if (!c->dry) {
+        if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
+        const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
+        float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
+        int rec;
+        int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
+        if (rc != DASGD_OK) return rc;
+        hipLaunchKernelGGL((k_merge<false>), dim3((unsigned)c->lay.n_chunks), dim3(kThreads), 0, c->main_s, chunks, xp,
+                           avg_ptr(c, slot), c->n_tensors, c->W, 1.0f - c->xi);
+        HIPCHK(c, hipGetLastError());
+        rc = prof_close(c, c->main_s, rec);
+        if (rc != DASGD_OK) return rc;
+    }
+    c->pending.pop_front();
+    return DASGD_OK;
+}
+
+int dasgd_query(const dasgd_ctx *c, int64_t *step_k, int *n_pending, int *bdue, int *mdue)
+{
+    if (!c) return DASGD_EINVAL;
+    if (step_k) *step_k = c->n_done - 1;
+    if (n_pending) *n_pending = (int)c->pending.size();
+    if (bdue) *bdue = c->bound && begin_due(c) ? 1 : 0;
+    if (mdue) *mdue = c->bound && merge_due(c) ? 1 : 0;
+    return DASGD_OK;
+}
+
+int dasgd_layout(const dasgd_ctx *c, int64_t *flat_offset, int64_t *P_padded)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->bound) return DASGD_ESTATE;
+    if (flat_offset) std::memcpy(flat_offset, c->lay.foff.data(), sizeof(int64_t) * (size_t)c->n_tensors);
+    if (P_padded) *P_padded = c->lay.P_pad;
+    return DASGD_OK;
+}
+
+int dasgd_pending_average(const dasgd_ctx *c, int which, int64_t *launch_step, size_t *byte_offset)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->bound) return DASGD_ESTATE;
+    if (which < 0 || which >= (int)c->pending.size()) return DASGD_EINVAL;
+    const Pending &p = c->pending[(size_t)which];
+    if (launch_step) *launch_step = p.launch_step;
+    if (byte_offset) *byte_offset = c->lay.A + sizeof(float) * (size_t)p.slot * (size_t)c->lay.P_pad;
+    return DASGD_OK;
+}
+
+int dasgd_profile(dasgd_ctx *c, int enable, int max_records)
+{
+    if (!c || (enable && max_records < 1)) return DASGD_EINVAL;
+    if (!c->bound || c->dry) return DASGD_ESTATE;
+    c->prof = enable != 0;
+    c->prof_max = enable ? max_records : 0;
+    return DASGD_OK;
+}
+
+int dasgd_profile_read(dasgd_ctx *c, int kernel, double *total_ms, int64_t *launches)
+{
+    if (!c || kernel < 0 || kernel >= DASGD_K_COUNT) return DASGD_EINVAL;
+    if (!c->bound || c->dry) return DASGD_ESTATE;
+    HIPCHK(c, hipStreamSynchronize(c->main_s));
+    HIPCHK(c, hipStreamSynchronize(c->side_s));
+    double sum = 0.0;
+    int64_t n = 0;
+    std::vector<ProfRec> keep;
+    for (const ProfRec &r : c->prof_recs) {
+        if (r.kernel != kernel) { keep.push_back(r); continue; }
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, r.start, r.stop));
+        sum += ms;
+        n += 1;
+        c->prof_pool.push_back(r);
+    }
+    c->prof_recs.swap(keep);
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = n;
+    return DASGD_OK;
+}
+
+int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
+
+void dasgd_destroy(dasgd_ctx *c)
+{
+    if (!c) return;
+    if (!c->dry) {
+        if (c->bound) {
+            (void)hipStreamSynchronize(c->main_s);
+            (void)hipStreamSynchronize(c->side_s);
+        }
+        // a bind that failed half-way leaves some of these set: release whatever exists
+        for (hipEvent_t e : c->snap_done) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : c->avg_done) if (e) (void)hipEventDestroy(e);
+        for (int b = 0; b < kGTables; ++b) if (c->g_ev[b]) (void)hipEventDestroy(c->g_ev[b]);
+        for (const ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (const ProfRec &r : c->prof_pool) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        if (c->g_pinned) (void)hipHostFree(c->g_pinned);
+    }
+    delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+"""The C ABI without a GPU: exported symbols, argument validation, and the host-side state machine
+(step counter, pending-average ring, due / overdue rules) in dry-run mode."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import paper_2006_00441_amd as pkg
+from paper_2006_00441_amd import DaSGD, DasgdError
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_in_header():
+    text = open(os.path.join(ROOT, "include", "dasgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dasgd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_in_header()
+    assert len(names) >= 15 and "dasgd_local_step" in names
+    assert sorted(pkg.EXPORTS) == names, "binding and header disagree"
+    L = pkg.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    out = subprocess.run(["nm", "-D", "--defined-only", pkg.library_path()], capture_output=True, text=True).stdout
+    exported = set(re.findall(r" T (dasgd_[a-z_]+)", out))
+    assert exported == set(names)
+
+
+def test_library_has_gfx950_code_object():
+    data = open(pkg.library_path(), "rb").read()
+    assert b"gfx950" in data
+
+
+def test_create_validates_arguments():
+    ok = dict(W=4, P=100, d=1, tau=1, lr=0.1, momentum=0.9, wd=1e-4)
+    DaSGD(**ok).destroy()
+    bad = [dict(W=0), dict(P=0), dict(d=-1), dict(tau=0), dict(lr=float("nan")), dict(lr=-1.0),
+           dict(momentum=1.0), dict(momentum=-0.1), dict(wd=-1.0), dict(wd=float("inf"))]
+    for b in bad:
+        with pytest.raises(DasgdError):
+            DaSGD(**{**ok, **b})
+    o = DaSGD(**ok)
+    for xi in (-0.1, 1.5, float("nan")):
+        with pytest.raises(DasgdError):
+            o.set_xi(xi)
+    o.set_xi(0.0); o.set_xi(1.0)
+    with pytest.raises(DasgdError):
+        o.set_lr(float("inf"))
+    with pytest.raises(DasgdError):
+        o.set_schedule(7)
+    o.destroy()
+
+
+def test_workspace_bytes_and_shapes():
+    o = DaSGD(8, 64 + 1000 + 5000, 2, 1, 0.1, 0.9, 0.0)
+    assert o.workspace_bytes([64, 1000, 5001]) == 0          # does not sum to P
+    assert o.workspace_bytes([64, 0, 6000]) == 0
+    n = o.workspace_bytes([64, 1000, 5000])
+    ppad = 64 + 1024 + 5056
+    slots = 3
+    assert n >= 4 * slots * (8 + 1) * ppad and n % 256 == 0
+    with pytest.raises(DasgdError) as e:
+        o.local_step(None)
+    assert e.value.code == pkg.DASGD_ESTATE                  # not bound
+    o.bind_dry_run([64, 1000, 5000])
+    assert o.layout() == ([0, 64, 64 + 1024], ppad)
+    with pytest.raises(DasgdError) as e:
+        o.bind_dry_run([64, 1000, 5000])
+    assert e.value.code == pkg.DASGD_ESTATE                  # already bound
+    o.destroy()
+
+
+@pytest.mark.parametrize("tau,d", [(1, 0), (1, 1), (1, 2), (1, 4), (4, 2), (3, 3), (2, 5), (4, 1), (5, 4)])
+def test_state_machine_follows_the_oracle_schedule(tau, d):
+    """The library's begin_due / merge_due sequence equals the oracle's launch / merge sequence."""
+    import oracle
+    o = DaSGD(2, 3, d, tau, 0.1, 0.0, 0.0)
+    o.bind_dry_run([3])
+    ref = oracle.Oracle(2, 3, d, tau, 0.1, 0.0, 0.0, np.zeros(3))
+    g = np.zeros((2, 3))
+    assert o.query() == (-1, 0, False, False)
+    for k in range(7 * tau + d + 2):
+        what = ref.step(g)
+        o.local_step(None)
+        kk, _, b, m0 = o.query()
+        assert kk == k and b == bool(what & 1)
+        if b:
+            o.average_begin()
+        _, npend, b2, m = o.query()
+        assert not b2 and m == bool(what & 2)
+        assert npend <= d // tau + 1
+        if m:
+            o.merge()
+        assert o.query()[1] == ref.n_pending
+    o.destroy(); ref.close()
+
+
+def test_illegal_call_orders_are_rejected():
+    E = pkg.DASGD_ESTATE
+    o = DaSGD(2, 8, 1, 2, 0.1, 0.9, 0.0)           # tau=2, d=1
+    o.bind_dry_run([8])
+
+    def fails(f):
+        with pytest.raises(DasgdError) as e:
+            f()
+        assert e.value.code == E
+
+    fails(o.average_begin)                          # before any local step
+    fails(o.merge)
+    o.local_step(None)                              # k=0: nothing due
+    fails(o.average_begin); fails(o.merge)
+    o.local_step(None)                              # k=1: begin due
+    fails(o.merge)                                  # nothing pending yet
+    fails(lambda: o.local_step(None))               # begin not issued
+    fails(lambda: o.set_schedule(pkg.SCHED_SERIAL))
+    o.average_begin()
+    fails(o.average_begin)                          # twice for the same step
+    fails(o.merge)                                  # launched at k=1, due at k=2
+    fails(lambda: o.set_schedule(pkg.SCHED_SERIAL)) # an average is pending
+    o.local_step(None)                              # k=2: merge due
+    fails(lambda: o.local_step(None))               # merge not issued
+    o.merge()
+    fails(o.merge)
+    assert o.query() == (2, 0, False, False)
+    o.set_schedule(pkg.SCHED_SERIAL)
+    o.destroy()
+
+
+def test_gpu_calls_fail_loudly_without_a_device():
+    """No GPU here: binding real memory must fail with an error, never fall back to anything."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    o = DaSGD(1, 4, 0, 1, 0.1, 0.0, 0.0)
+    with pytest.raises(RuntimeError):
+        o.bind_tensors([[torch.zeros(4)]], [[torch.zeros(4)]], None, None)
+    with pytest.raises(DasgdError):
+        o.profile(True)
+    o.destroy()
