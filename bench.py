@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the DaSGD per-step parameter pipeline on one MI355X.
+
+A step is one pass of the whole hot path over all W replicas: local step (with the fused snapshot
+store), launch of the W-way mean on the side stream, and the delayed merge.  The default workload
+is the ResNet-50-shaped set with W=8, tau=1, d=2 (every step launches an average and merges the one
+launched two steps earlier).  Inputs (weights, momentum, gradients) are resident in HBM before the
+timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_w8|resnet50_w16|bert_large_w4|quadratic]
+                    [--no-cpu-baseline] [--no-overlap-study] [--only-timed]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
+    """Bytes the method itself must move per replica-parameter (fp32), by kernel."""
+    return {"local_step": 20.0,                    # read x, v, g; write x, v
+            "local_step_snapshot": 24.0,           # + write the snapshot
+            "local_step_to_snapshot": 20.0,        # read x, v, g; write v and the snapshot (x is written by the merge)
+            "mean": 4.0 + 4.0 / W,                 # read W snapshot rows, write one average
+            "merge": 8.0 + 4.0 / W}[kernel]        # read x and the average (once), write x
+
+
+class Bench:
+    """Device state for one workload: W replicas of (x, v, g) in flat arenas plus a bound context."""
+
+    def __init__(self, cfg, schedule: int, gemm: bool = False):
+        import torch
+        import workloads as wl
+        import paper_2006_00441_amd as pkg
+        self.torch, self.pkg, self.cfg = torch, pkg, cfg
+        dev = torch.device("cuda:0")
+        self.main = torch.cuda.Stream(dev)
+        self.side = torch.cuda.Stream(dev)
+        W, P = cfg.W, cfg.P
+        off, n = cfg.params.offsets, cfg.params.n_tensors
+        with torch.cuda.stream(self.main):
+            w0 = wl.init_weights(cfg, dev)
+            self.x = w0.unsqueeze(0).repeat(W, 1).contiguous()
+            self.v = torch.zeros(W, P, device=dev)
+            self.g = torch.empty(W, P, device=dev)
+            if cfg.kind == "external":
+                sigma = wl.grad_sigma_vector(cfg, dev)
+                for j in range(W):
+                    wl.gradient(cfg, 0, j, dev, sigma=sigma, out=self.g[j])
+            else:
+                q = wl.QuadraticProblem.build(cfg, dev)
+                for j in range(W):
+                    self.g[j].copy_(q.grad(self.x[j], 0, j))
+            if gemm:   # forward/backward stand-in: bf16 GEMM 8192^3 from seeded N(0,1) data
+                ii = torch.arange(8192 * 8192, device=dev, dtype=torch.int64)
+                self.ga = wl.standard_normal(wl.stream_key(cfg.seed, 101), ii).view(8192, 8192).to(torch.bfloat16)
+                self.gb = wl.standard_normal(wl.stream_key(cfg.seed, 102), ii).view(8192, 8192).to(torch.bfloat16)
+                self.gc = torch.empty(8192, 8192, device=dev, dtype=torch.bfloat16)
+                del ii
+        self.gemm = gemm
+        view = lambda a: [[a[j, off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
+        self.opt = pkg.DaSGD(W, P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, xi=cfg.xi)
+        self.ws = self.opt.bind_tensors(view(self.x), view(self.v), self.main, self.side)
+        self.opt.set_schedule(schedule)
+        self.g_ptrs = pkg.DaSGD.grad_pointers(view(self.g))
+        self.first = True
+        self.main.synchronize()
+
+    def step(self):
+        if self.gemm:
+            with self.torch.cuda.stream(self.main):
+                self.torch.matmul(self.ga, self.gb, out=self.gc)
+        self.opt.step(self.g_ptrs if self.first else None)
+        self.first = False
+
+    def run(self, steps: int, warmup: int):
+        """Returns (wall seconds for `steps` steps, main-stream event milliseconds)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(self.main)
+        for _ in range(steps):
+            self.step()
+        e1.record(self.main)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return t1 - t0, e0.elapsed_time(e1)
+
+    def close(self):
+        self.opt.destroy()
+        for a in ("x", "v", "g", "ws", "ga", "gb", "gc"):
+            if hasattr(self, a):
+                delattr(self, a)
+        self.torch.cuda.empty_cache()
+
+
+def timed_region(cfg, steps: int, warmup: int):
+    """The headline measurement: overlap schedule, per-kernel event timing live in the timed region."""
+    import paper_2006_00441_amd as pkg
+    b = Bench(cfg, pkg.SCHED_OVERLAP)
+    for _ in range(warmup):
+        b.step()
+    b.opt.profile(True, 4 * steps + 16)
+    wall, ev_ms = b.run(steps, 0)
+    kernels = {}
+    for kid, name in pkg.KERNEL_NAMES.items():
+        ms, n = b.opt.profile_read(kid)
+        if n:
+            kernels[name] = {"launches": n, "avg_ms": ms / n}
+    b.opt.profile(False)
+    b.close()
+    return wall, ev_ms, kernels
+
+
+def overlap_study(cfg, steps: int, warmup: int, gemm: bool):
+    """Three schedules with identical kernels: S0 everything on one stream, S1 the mean on the side
+    stream, F = S0 without snapshot and mean (timing floor).  hidden = (T(S0)-T(S1)) / (T(S0)-T(F))."""
+    import paper_2006_00441_amd as pkg
+    t = {}
+    for name, sched in (("S0_serial", pkg.SCHED_SERIAL), ("S1_overlap", pkg.SCHED_OVERLAP),
+                        ("F_no_average", pkg.SCHED_NO_AVERAGE_TIMING_ONLY)):
+        b = Bench(cfg, sched, gemm=gemm)
+        best = min(b.run(steps, warmup if r == 0 else 2)[0] for r in range(3))
+        t[name] = best / steps * 1e3
+        b.close()
+    t_avg = t["S0_serial"] - t["F_no_average"]
+    hidden = (t["S0_serial"] - t["S1_overlap"]) / t_avg if t_avg > 0 else None
+    return {"gemm_8192_bf16_per_step": gemm, "ms_per_step": {k: round(v, 4) for k, v in t.items()},
+            "averaging_ms": round(t_avg, 4), "hidden_frac": None if hidden is None else round(hidden, 4),
+            "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4)}
+
+
+def cpu_baseline(cfg, budget_s: float = 12.0):
+    """The CPU oracle (fp32 variant, as it stands) timed on this machine's host cores on a bounded number
+    of steps of the same workload at full size."""
+    import numpy as np
+    import torch
+    import oracle
+    import workloads as wl
+    cores = len(os.sched_getaffinity(0))
+    threads = oracle.set_threads(cores)
+    dev = torch.device("cuda:0")
+    sigma = wl.grad_sigma_vector(cfg, dev) if cfg.kind == "external" else None
+    g = np.empty((cfg.W, cfg.P), dtype=np.float32)
+    for j in range(cfg.W):
+        if sigma is not None:
+            g[j] = wl.gradient(cfg, 0, j, dev, sigma=sigma).cpu().numpy()
+        else:
+            g[j] = 0.01
+    w0 = wl.init_weights(cfg, dev).cpu().numpy()
+    del sigma
+    torch.cuda.empty_cache()
+    o = oracle.Oracle(cfg.W, cfg.P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, w0, xi=cfg.xi, dtype="f32")
+    for _ in range(cfg.d + 1):            # reach the steady state where every kind of step occurs
+        o.step(g)
+    t0 = time.perf_counter(); o.step(g); one = time.perf_counter() - t0
+    n = int(max(3, min(200, budget_s / max(one, 1e-6))))
+    n = max(cfg.tau, n // cfg.tau * cfg.tau)
+    t0 = time.perf_counter()
+    for _ in range(n):
+        o.step(g)
+    dt = time.perf_counter() - t0
+    o.close()
+    return {"value": cfg.W * cfg.P * n / dt, "unit": "replica-params/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} steps of {cfg.name} at full size (W={cfg.W}, P={cfg.P}), fp32 oracle, "
+                      f"{threads} OpenMP threads, {dt:.1f} s", "ms_per_step": dt / n * 1e3}
+
+
+def pmc_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50_w8")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap-study", action="store_true")
+    ap.add_argument("--only-timed", action="store_true", help="just the timed region (for profilers)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the DaSGD pipeline on ONE GPU (W replicas share its HBM); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as wl
+    import paper_2006_00441_amd as pkg
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU implementation of this path", file=sys.stderr)
+        return 2
+    pkg.lib()
+    cfg = wl.get_config(args.workload)
+    rp = cfg.W * cfg.P
+
+    wall, ev_ms, kernels = timed_region(cfg, args.steps, args.warmup)
+    ms_per_step = wall / args.steps * 1e3
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
+    for name, k in kernels.items():
+        b = algorithmic_bytes_per_rp(name, cfg.W) * rp
+        k["algorithmic_bytes"] = b
+        k["GBps"] = b / (k["avg_ms"] * 1e-3) / 1e9
+        k["frac_of_hbm_peak"] = k["GBps"] / HBM_PEAK_GBS
+    d = kernels[dom]
+    out = {
+        "metric": "replica-params updated/s + achieved HBM GB/s; % averaging time hidden",
+        "value": rp * args.steps / wall,
+        "unit": "replica-params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "ms_per_step_main_stream_events": ev_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.params.name}-shaped, {cfg.params.n_tensors} fp32 tensors, "
+                               f"P={cfg.P}, W={cfg.W}, tau={cfg.tau}, d={cfg.d}, xi={cfg.xi}",
+                   "schedule": "overlap (mean on side stream)", "replica_params": rp},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": d["frac_of_hbm_peak"], "avg_ms": d["avg_ms"], "launches": d["launches"],
+                     "algorithmic_bytes_per_launch": d["algorithmic_bytes"],
+                     "traffic": pmc_traffic(dom, cfg.name)},
+        "kernels": {n: {"avg_ms": round(k["avg_ms"], 5), "launches": k["launches"], "GBps": round(k["GBps"], 1),
+                        "frac_of_hbm_peak": round(k["frac_of_hbm_peak"], 4)} for n, k in kernels.items()},
+    }
+    step_bytes = sum(k["algorithmic_bytes"] * k["launches"] for k in kernels.values()) / args.steps
+    out["whole_step"] = {"algorithmic_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if not args.only_timed and not args.no_overlap_study:
+        k = max(20, min(args.steps, 100))
+        out["overlap"] = {"hbm_bound_steps_only": overlap_study(cfg, k, 10, gemm=False),
+                          "with_compute_stand_in": overlap_study(cfg, k, 10, gemm=True)}
+    if not args.only_timed and not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -61,11 +61,12 @@ enum {
 
 /* Kernels for dasgd_profile_read. */
 enum {
-    DASGD_K_LOCAL_STEP      = 0, /* local step without snapshot store */
-    DASGD_K_LOCAL_STEP_SNAP = 1, /* local step that also stores the snapshot */
-    DASGD_K_MEAN            = 2, /* W-way replica mean */
-    DASGD_K_MERGE           = 3, /* delayed merge */
-    DASGD_K_COUNT           = 4
+    DASGD_K_LOCAL_STEP         = 0, /* local step storing x, v                      (20 B per element) */
+    DASGD_K_LOCAL_STEP_SNAP    = 1, /* local step storing x, v and the snapshot     (24 B per element) */
+    DASGD_K_MEAN               = 2, /* W-way replica mean                            (4 + 4/W)         */
+    DASGD_K_MERGE              = 3, /* delayed merge                                 (8 + 4/W)         */
+    DASGD_K_LOCAL_STEP_TO_SNAP = 4, /* local step storing v and the snapshot only   (20 B per element) */
+    DASGD_K_COUNT              = 5
 };
 
 /* Create a context for W replicas of P fp32 parameters each.
@@ -123,22 +124,33 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  *     g' = g + wd x ;  v <- momentum v + g' ;  x <- x - lr v
  * one fused kernel over all replicas and tensors on main_stream.  When (k+1) mod tau == 0 the
  * same kernel also stores the new weights into a snapshot slot for the average that
- * dasgd_average_begin will launch.
+ * dasgd_average_begin will launch.  When, in addition, a merge is due at this same step, the
+ * kernel stores the new weights ONLY into the snapshot and dasgd_merge reads them from there:
+ * x then holds the finished x_{k+1} only after this step's dasgd_merge (which the caller has to
+ * issue before the next local step anyway).
  *   g   [W * n_tensors] host array of device pointers (same order and shapes as x), read only;
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
  *       pointers of the previous call (the table is re-uploaded only when it changes).
+ * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
+ * in the order given, replica rows back to back, base 16-byte aligned, P a multiple of 4 -- the
+ * kernels address them by arithmetic alone (fastest); any other layout goes through a chunk
+ * table.  Results are identical.
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
 int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
 
 /* Launch the average of the weights as they were right after the latest local step (Eq. 2's
  * summand x - eta g; matrix form (X - eta G) J in the appendix): A = (1/W) sum_j snapshot_j, on
- * side_stream after main_stream's local step, occupying a ring slot until merged.
+ * side_stream after main_stream's local step, occupying a ring slot until merged.  When a merge of
+ * an older average is due at this same step, the launch is held back until that merge has been
+ * enqueued (the mean has d steps of slack, the merge none), so that the mean runs beside the
+ * caller's next forward/backward pass rather than beside the merge.
  * ESTATE: not due (legal exactly once after a local step k with (k+1) mod tau == 0). */
 int dasgd_average_begin(dasgd_ctx *ctx);
 
 /* Fold the oldest pending average into every replica (Eq. 2, second branch):
  *     x_j <- xi x_j + (1 - xi) A        computed as x_j + (1 - xi)(A - x_j)
- * on main_stream, after a device-side wait for that average; frees its slot.
+ * on main_stream, after a device-side wait for that average; frees its slot.  If this step's own
+ * average is still to be launched (see dasgd_average_begin) it is launched right behind the merge.
  * ESTATE: no pending average, or the oldest one was not launched at step k - d. */
 int dasgd_merge(dasgd_ctx *ctx);
 
@@ -149,7 +161,8 @@ int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begi
 
 /* Layout of the library-owned buffers inside the workspace, for inspection by tests and tools:
  * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
- * *P_padded = elements per row.  ESTATE if not bound. */
+ * *P_padded = elements per row: P when x and v were bound as W x P matrices (rows mirror that
+ * layout), otherwise every tensor padded to a multiple of 64 elements.  ESTATE if not bound. */
 int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
 
 /* Locate pending average number `which` (0 = oldest): its launch step and the byte offset of its

@@ -16,9 +16,9 @@ from . import build as _build
 
 DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
 SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY = 0, 1, 2
-K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE = 0, 1, 2, 3
+K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, K_LOCAL_STEP_TO_SNAP = 0, 1, 2, 3, 4
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
-                K_MEAN: "mean", K_MERGE: "merge"}
+                K_MEAN: "mean", K_MERGE: "merge", K_LOCAL_STEP_TO_SNAP: "local_step_to_snapshot"}
 _ERR = {DASGD_EINVAL: "DASGD_EINVAL (bad argument)", DASGD_ESTATE: "DASGD_ESTATE (call illegal in this state)",
         DASGD_ENOMEM: "DASGD_ENOMEM (workspace too small)", DASGD_EHIP: "DASGD_EHIP (HIP call failed)"}
 

@@ -33,8 +33,9 @@ struct ProfRec {
 
 struct Layout {                     // byte offsets into the workspace
     size_t chunks, xp, vp, gp[kGTables], S, A, total;
-    int64_t P_pad, n_chunks;
-    std::vector<int64_t> foff;
+    int64_t P_pad, n_chunks;        // P_pad: elements per snapshot row / average
+    std::vector<int64_t> foff;      // start of each tensor inside such a row
+    bool flat = false;              // rows are unpadded (foff = plain prefix sums, P_pad = P)
 };
 
 }  // namespace
@@ -64,7 +65,13 @@ struct dasgd_ctx {
     int64_t n_launched = 0;         // averages launched so far
     bool begun_for_k = false;       // dasgd_average_begin already issued for the current k
     bool snap_valid = false;        // the latest local step stored a snapshot
+    bool y_in_snap = false;         // ... and ONLY the snapshot: x is stale until this step's merge
+    bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
     int snap_slot = 0;
+    // matrix layout: x, v (and g) are W x P row-major matrices, rows back to back, 16-byte aligned
+    bool xv_matrix = false, g_matrix = false;
+    float *x0 = nullptr, *v0 = nullptr;
+    const float *g0 = nullptr;
     std::deque<Pending> pending;
     std::vector<hipEvent_t> snap_done, avg_done;
     // profiling
@@ -97,17 +104,24 @@ bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
     return sum == c->P;
 }
 
-Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
+// Rows of the library-owned buffers either pad every tensor to a 256-byte boundary (so the table
+// kernels can always use 128-bit accesses on them) or, when the caller's x and v are plain W x P
+// matrices, mirror that unpadded layout (so one flat index addresses x, v, g and the snapshot alike).
+// The byte offsets of the padded layout are used in both cases: the workspace size must not depend
+// on pointers that dasgd_workspace_bytes never sees.
+Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false)
 {
     Layout L;
     L.foff.resize(n_tensors);
-    int64_t f = 0, nch = 0;
+    int64_t f = 0, fp = 0, nch = 0;
     for (int t = 0; t < n_tensors; ++t) {
-        L.foff[t] = f;
+        L.foff[t] = flat ? fp : f;
+        fp += numel[t];
         f += (numel[t] + kPad - 1) / kPad * kPad;
         nch += (numel[t] + kChunk - 1) / kChunk;
     }
-    L.P_pad = f;
+    L.flat = flat;
+    L.P_pad = f;                    // sizes below always use the padded row length
     L.n_chunks = nch;
     const size_t tbl = sizeof(void *) * (size_t)c->W * (size_t)n_tensors;
     size_t o = 0;
@@ -118,7 +132,24 @@ Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
     L.S = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)c->W * (size_t)L.P_pad);
     L.A = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)L.P_pad);
     L.total = o;
+    if (flat) L.P_pad = fp;
     return L;
+}
+
+// True when ptr[j*n + t] == ptr[0] + j*P + (unpadded offset of t) for all j, t, base 16-byte aligned
+// and P a multiple of 4: a W x P row-major matrix with rows back to back.
+template <typename T>
+bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr)
+{
+    if (c->P % 4 != 0 || (reinterpret_cast<uintptr_t>(ptr[0]) & 15u)) return false;
+    for (int j = 0; j < c->W; ++j) {
+        int64_t off = 0;
+        for (int t = 0; t < n_tensors; ++t) {
+            if (ptr[(size_t)j * n_tensors + t] != ptr[0] + (int64_t)j * c->P + off) return false;
+            off += numel[t];
+        }
+    }
+    return true;
 }
 
 inline float *snap_ptr(const dasgd_ctx *c, int slot)
@@ -171,14 +202,14 @@ int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A)
     const v4f *S4 = reinterpret_cast<const v4f *>(S);
     v4f *A4 = reinterpret_cast<v4f *>(A);
     const float inv_w = 1.0f / (float)c->W;
-    auto grid = [&](int U) { return dim3((unsigned)((n4 + (int64_t)kThreads * U - 1) / ((int64_t)kThreads * U))); };
+    auto grid = [&](int U) { return dim3((unsigned)((n4 + (int64_t)kWave * U - 1) / ((int64_t)kWave * U))); };
     switch (c->W) {
-    case 1:  hipLaunchKernelGGL((k_mean<1, 4, true>),  grid(4), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 2:  hipLaunchKernelGGL((k_mean<2, 4, true>),  grid(4), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 4:  hipLaunchKernelGGL((k_mean<4, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 8:  hipLaunchKernelGGL((k_mean<8, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 16: hipLaunchKernelGGL((k_mean<16, 1, true>), grid(1), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    default: hipLaunchKernelGGL((k_mean<0, 2, true>),  grid(2), dim3(kThreads), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 1:  hipLaunchKernelGGL((k_mean<1, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 2:  hipLaunchKernelGGL((k_mean<2, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 4:  hipLaunchKernelGGL((k_mean<4, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 8:  hipLaunchKernelGGL((k_mean<8, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 16: hipLaunchKernelGGL((k_mean<16, 1, true>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    default: hipLaunchKernelGGL((k_mean<0, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
     }
     HIPCHK(c, hipGetLastError());
     return DASGD_OK;
@@ -263,7 +294,8 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         if (!x[r] || !v[r]) return DASGD_EINVAL;
         if ((reinterpret_cast<uintptr_t>(x[r]) | reinterpret_cast<uintptr_t>(v[r])) & 3u) return DASGD_EINVAL;
     }
-    Layout L = make_layout(c, n_tensors, numel);
+    const bool matrix = is_matrix(c, n_tensors, numel, x) && is_matrix(c, n_tensors, numel, v);
+    Layout L = make_layout(c, n_tensors, numel, matrix);
     if (workspace_bytes < L.total) return DASGD_ENOMEM;
 
     // chunk table
@@ -282,6 +314,9 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     c->n_tensors = n_tensors;
     c->numel.assign(numel, numel + n_tensors);
     c->lay = L;
+    c->xv_matrix = matrix;
+    c->x0 = x[0];
+    c->v0 = v[0];
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
@@ -313,14 +348,40 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     return DASGD_OK;
 }
 
+// Launch the W-way mean of snapshot slot `slot`.  In the overlap schedule it goes to the side
+// stream, ordered after everything enqueued on the main stream so far.
+static int launch_average(dasgd_ctx *c, int slot)
+{
+    hipStream_t s = c->main_s;
+    if (c->schedule == DASGD_SCHED_OVERLAP) {
+        HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
+        HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
+        s = c->side_s;
+    }
+    int rec;
+    int rc = prof_open(c, DASGD_K_MEAN, s, &rec);
+    if (rc != DASGD_OK) return rc;
+    rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot));
+    if (rc != DASGD_OK) return rc;
+    rc = prof_close(c, s, rec);
+    if (rc != DASGD_OK) return rc;
+    if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
+    return DASGD_OK;
+}
+
 int dasgd_local_step(dasgd_ctx *c, const float *const *g)
 {
     if (!c) return DASGD_EINVAL;
     if (!c->bound) return DASGD_ESTATE;
     if (begin_due(c) || merge_due(c)) return DASGD_ESTATE;          // unfinished business of step k
-    const bool snap = ((c->n_done + 1) % c->tau) == 0 && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
-    const bool snap_step = ((c->n_done + 1) % c->tau) == 0;
+    const int64_t k = c->n_done;                                    // the step being taken
+    const bool snap_step = ((k + 1) % c->tau) == 0;
     if (snap_step && (int)c->pending.size() >= c->slots) return DASGD_ESTATE;
+    // will this very step end with a merge?  (d == 0: of the average it launches itself)
+    const bool merge_follows = (c->d == 0) ? snap_step
+                                           : (!c->pending.empty() && c->pending.front().launch_step == k - c->d);
+    int mode = kStoreX;
+    if (snap_step && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) mode = merge_follows ? kStoreS : kStoreXS;
     const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
 
     if (!c->dry) {
@@ -345,23 +406,41 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 HIPCHK(c, hipMemcpyAsync(c->ws + c->lay.gp[b], stage, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
                 c->g_cached.assign(g, g + rows);
                 c->g_cur = b;
+                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g);
+                c->g0 = g[0];
             }
         }
-        const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
-        float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
-        float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
-        const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
-        const dim3 grid((unsigned)c->lay.n_chunks, (unsigned)c->W);
         const int slot = (int)(c->n_launched % c->slots);
+        float *S = mode == kStoreX ? nullptr : snap_ptr(c, slot);
+        const int kid = mode == kStoreX ? DASGD_K_LOCAL_STEP
+                      : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
         int rec;
-        int rc = prof_open(c, snap ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP, c->main_s, &rec);
+        int rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        if (snap)
-            hipLaunchKernelGGL((k_local_step<true, true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp,
-                               snap_ptr(c, slot), c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
-        else
-            hipLaunchKernelGGL((k_local_step<false, true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp,
-                               (float *)nullptr, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+        if (c->xv_matrix && c->g_matrix) {
+            const int64_t n4 = (int64_t)c->W * c->P / 4;
+            const dim3 grid((unsigned)((n4 + kWave - 1) / kWave));
+            v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0), *s4 = reinterpret_cast<v4f *>(S);
+            const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
+            if (mode == kStoreX)
+                hipLaunchKernelGGL((k_local_step_flat<kStoreX>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
+            else if (mode == kStoreXS)
+                hipLaunchKernelGGL((k_local_step_flat<kStoreXS>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
+            else
+                hipLaunchKernelGGL((k_local_step_flat<kStoreS>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
+        } else {
+            const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
+            float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
+            float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
+            const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
+            const dim3 grid((unsigned)c->lay.n_chunks, (unsigned)c->W);
+            if (mode == kStoreX)
+                hipLaunchKernelGGL((k_local_step<kStoreX>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+            else if (mode == kStoreXS)
+                hipLaunchKernelGGL((k_local_step<kStoreXS>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+            else
+                hipLaunchKernelGGL((k_local_step<kStoreS>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+        }
         HIPCHK(c, hipGetLastError());
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
@@ -369,6 +448,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     c->n_done += 1;
     c->begun_for_k = false;
     c->snap_valid = snap_step;
+    c->y_in_snap = (mode == kStoreS);
+    c->mean_deferred = false;
     c->snap_slot = (int)(c->n_launched % c->slots);
     return DASGD_OK;
 }
@@ -380,20 +461,16 @@ int dasgd_average_begin(dasgd_ctx *c)
     if ((int)c->pending.size() >= c->slots) return DASGD_ESTATE;
     const int slot = c->snap_slot;
     if (!c->dry && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) {
-        hipStream_t s = c->main_s;
-        if (c->schedule == DASGD_SCHED_OVERLAP) {
-            HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
-            HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
-            s = c->side_s;
+        // The mean has d local steps of slack, the merge of this step has none: when a merge of an
+        // OLDER average is still to come in this step, the mean is launched right behind it, so the
+        // two bandwidth-bound kernels do not run against each other and the mean overlaps what the
+        // caller enqueues next (the forward/backward pass of the following local step).
+        if (c->d > 0 && merge_due(c)) {
+            c->mean_deferred = true;
+        } else {
+            int rc = launch_average(c, slot);
+            if (rc != DASGD_OK) return rc;
         }
-        int rec;
-        int rc = prof_open(c, DASGD_K_MEAN, s, &rec);
-        if (rc != DASGD_OK) return rc;
-        rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot));
-        if (rc != DASGD_OK) return rc;
-        rc = prof_close(c, s, rec);
-        if (rc != DASGD_OK) return rc;
-        if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
     }
     c->pending.push_back(Pending{c->n_done - 1, slot});
     c->n_launched += 1;
@@ -408,17 +485,45 @@ int dasgd_merge(dasgd_ctx *c)
     const int slot = c->pending.front().slot;
     if (!c->dry) {
         if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
-        const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
-        float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
+        const float *Y = c->y_in_snap ? snap_ptr(c, c->snap_slot) : nullptr;
+        const float om = 1.0f - c->xi;
         int rec;
         int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        hipLaunchKernelGGL((k_merge<false>), dim3((unsigned)c->lay.n_chunks), dim3(kThreads), 0, c->main_s, chunks, xp,
-                           avg_ptr(c, slot), c->n_tensors, c->W, 1.0f - c->xi);
+        if (c->xv_matrix) {
+            const int64_t row4 = c->P / 4;
+            const int64_t pieces = (row4 + kWave - 1) / kWave;
+            const dim3 grid((unsigned)((pieces + 7) / 8 * 8 * c->W));
+            v4f *X4 = reinterpret_cast<v4f *>(c->x0);
+            const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
+            const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
+            switch (c->W) {
+            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            }
+        } else {
+            const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
+            float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
+            const dim3 grid((unsigned)c->lay.n_chunks);
+            if (Y)
+                hipLaunchKernelGGL((k_merge<true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
+            else
+                hipLaunchKernelGGL((k_merge<false>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
+        }
         HIPCHK(c, hipGetLastError());
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
+        if (c->mean_deferred) {
+            rc = launch_average(c, c->snap_slot);
+            if (rc != DASGD_OK) return rc;
+        }
     }
+    c->mean_deferred = false;
+    c->y_in_snap = false;
     c->pending.pop_front();
     return DASGD_OK;
 }

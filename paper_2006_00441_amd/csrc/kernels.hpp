@@ -1,12 +1,20 @@
 // Device code of the DaSGD parameter pipeline for gfx950 (CDNA4, 64-wide wavefronts).
 //
-// All three kernels are pure streaming passes bound by HBM bandwidth (<= 0.3 flop per byte), so
-// the design is about memory traffic only: 128-bit accesses, several independent loads in
-// flight per lane before the first use, every byte touched once, no LDS, no MFMA.
+// All kernels are pure streaming passes bound by HBM bandwidth (<= 0.3 flop per byte), so the
+// design is about memory traffic only: 128-bit accesses, every byte touched once, non-temporal
+// hints on everything that streams, no LDS, no MFMA.
 //
-//   k_local_step   x, v, g -> x, v [, snapshot]        (paper Eq. 2, first branch; Section 4.1)
-//   k_mean         snapshot rows -> average             ((X - eta G) J of the matrix form, appendix)
-//   k_merge        x, average -> x                      (Eq. 2, second branch)
+//   local step   x, v, g -> x, v [, snapshot]        (paper Eq. 2, first branch; Section 4.1)
+//   mean         snapshot rows -> average             ((X - eta G) J of the matrix form, appendix)
+//   merge        y, average -> x                      (Eq. 2, second branch)
+//
+// Two families.  The "matrix" kernels (k_*_flat) serve the layout the paper's matrix form suggests:
+// X, V, G are W x P row-major matrices (one row per replica, rows back to back).  They address by
+// pure arithmetic and run one 64-lane wavefront per workgroup with one 128-bit access per lane per
+// array: measured on MI355X this shape sustains the highest HBM throughput (short-lived single-wave
+// workgroups keep the memory system evenly fed; anything that delays a wave's first load -- a
+// descriptor fetch, a larger workgroup -- costs bandwidth).  The "table" kernels (k_local_step,
+// k_merge) serve arbitrary per-tensor pointers through a chunk table.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -29,6 +37,14 @@ struct Chunk {
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+
+// What a local step stores besides the momentum buffer.
+enum : int {
+    kStoreX  = 0,   // x only                      (no average is launched after this step)
+    kStoreXS = 1,   // x and the snapshot          (an average is launched, no merge follows this step)
+    kStoreS  = 2    // the snapshot only           (a merge follows in the same step and reads the
+                    //                              snapshot, so x need not hold the intermediate value)
+};
 
 template <bool NT> __device__ __forceinline__ v4f ld4(const v4f *p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
@@ -58,25 +74,27 @@ __device__ __forceinline__ void sgd4(v4f &x, v4f &v, const v4f g, float lr, floa
 }
 
 // ------------------------------------------------------------------------------------------------
-// Local step on every replica: grid = (chunks, W).  20 bytes per element (24 with the snapshot).
-template <bool SNAP, bool NT>
+// Local step on every replica through the chunk table: grid = (chunks, W).
+// 20 bytes per element (24 when both x and the snapshot are stored).
+template <int MODE>
 __global__ void __launch_bounds__(kThreads)
 k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, float *const *__restrict__ vp,
              const float *const *__restrict__ gp, float *__restrict__ S, int64_t P_pad, int n_tensors,
              float lr, float momentum, float wd)
 {
+    constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
     const Chunk c = chunks[blockIdx.x];
     const int j = blockIdx.y;
     const int64_t row = (int64_t)j * n_tensors + c.tensor;
     float *__restrict__ x = xp[row] + c.off;
     float *__restrict__ v = vp[row] + c.off;
     const float *__restrict__ g = gp[row] + c.off;
-    float *__restrict__ s = SNAP ? S + (int64_t)j * P_pad + c.foff : nullptr;
+    float *__restrict__ s = WS ? S + (int64_t)j * P_pad + c.foff : nullptr;
     const int tid = threadIdx.x;
     const int len = c.len;
 
     const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(v) |
-                           reinterpret_cast<uintptr_t>(g)) & 15u) == 0;
+                           reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(s)) & 15u) == 0;
     if (aligned) {
         v4f *x4 = reinterpret_cast<v4f *>(x);
         v4f *v4 = reinterpret_cast<v4f *>(v);
@@ -87,17 +105,17 @@ k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, fl
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int i = tid + u * kThreads;
-                xr[u] = ld4<false>(x4 + i);
-                vr[u] = ld4<false>(v4 + i);
-                gr[u] = ld4<NT>(g4 + i);
+                xr[u] = ld4<true>(x4 + i);
+                vr[u] = ld4<true>(v4 + i);
+                gr[u] = ld4<true>(g4 + i);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int i = tid + u * kThreads;
                 sgd4(xr[u], vr[u], gr[u], lr, momentum, wd);
-                st4<false>(x4 + i, xr[u]);
-                st4<false>(v4 + i, vr[u]);
-                if (SNAP) st4<NT>(s4 + i, xr[u]);
+                if (WX) st4<true>(x4 + i, xr[u]);
+                st4<true>(v4 + i, vr[u]);
+                if (WS) st4<true>(s4 + i, xr[u]);
             }
         } else {
             const int n4 = len >> 2;
@@ -105,28 +123,49 @@ k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, fl
                 v4f xr = x4[i], vr = v4[i];
                 const v4f gr = g4[i];
                 sgd4(xr, vr, gr, lr, momentum, wd);
-                x4[i] = xr;
+                if (WX) x4[i] = xr;
                 v4[i] = vr;
-                if (SNAP) s4[i] = xr;
+                if (WS) s4[i] = xr;
             }
             const int e = (n4 << 2) + tid;         // at most 3 leftover elements
             if (e < len) {
                 float xs = x[e], vs = v[e];
                 sgd1(xs, vs, g[e], lr, momentum, wd);
-                x[e] = xs;
+                if (WX) x[e] = xs;
                 v[e] = vs;
-                if (SNAP) s[e] = xs;
+                if (WS) s[e] = xs;
             }
         }
     } else {
         for (int e = tid; e < len; e += kThreads) {
             float xs = x[e], vs = v[e];
             sgd1(xs, vs, g[e], lr, momentum, wd);
-            x[e] = xs;
+            if (WX) x[e] = xs;
             v[e] = vs;
-            if (SNAP) s[e] = xs;
+            if (WS) s[e] = xs;
         }
     }
+}
+
+// Matrix layout: x, v, g (and the snapshot) are W*P contiguous floats each, 16-byte aligned, with
+// n4 = W*P/4.  One wavefront per workgroup, one 128-bit access per lane per array.
+constexpr int kWave = 64;
+
+template <int MODE>
+__global__ void __launch_bounds__(kWave)
+k_local_step_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
+                  int64_t n4, float lr, float momentum, float wd)
+{
+    constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (i >= n4) return;
+    v4f xr = ld4<true>(x + i);
+    v4f vr = ld4<true>(v + i);
+    const v4f gr = ld4<true>(g + i);
+    sgd4(xr, vr, gr, lr, momentum, wd);
+    if (WX) st4<true>(x + i, xr);
+    st4<true>(v + i, vr);
+    if (WS) st4<true>(s + i, xr);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -141,18 +180,18 @@ template <int LO, int HI> __device__ __forceinline__ v4f tree_sum(const v4f *r) 
 
 // W-way replica mean over library-owned rows: A[i] = (1/W) sum_j S[j][i].  One lane owns one
 // 128-bit column and reads it from all W rows (W independent loads in flight), so the reduction
-// needs no cross-lane traffic.  (4 + 4/W) bytes per replica-element.  WT > 0: W known at compile
+// needs no cross-lane traffic.  (4 + 4/W) bytes per replica-element.  Single-wave workgroups.  WT > 0: W known at compile
 // time, the whole column set is loaded before the tree sum; WT == 0: any W, four rows at a time.
 template <int WT, int U, bool NT>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kWave)
 k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4, int W, float inv_w)
 {
-    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * (kWave * U) + threadIdx.x;
     if constexpr (WT > 0) {
         v4f r[U][WT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kThreads;
+            const int64_t i = base + (int64_t)u * kWave;
             if (i < n4) {
 #pragma unroll
                 for (int j = 0; j < WT; ++j) r[u][j] = ld4<NT>(S + (int64_t)j * row4 + i);
@@ -160,13 +199,13 @@ k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4,
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kThreads;
+            const int64_t i = base + (int64_t)u * kWave;
             if (i < n4) st4<false>(A + i, tree_sum<0, WT>(r[u]) * inv_w);
         }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kThreads;
+            const int64_t i = base + (int64_t)u * kWave;
             if (i >= n4) continue;
             v4f acc = {0.f, 0.f, 0.f, 0.f};
             int j = 0;
@@ -184,8 +223,10 @@ k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4,
 }
 
 // ------------------------------------------------------------------------------------------------
-// Delayed merge: x_j <- x_j + (1 - xi)(A - x_j) for every replica j; grid = chunks.  The chunk of A
-// is read once into registers and applied to all W replicas: (8 + 4/W) bytes per replica-element.
+// Delayed merge: x_j <- y_j + (1 - xi)(A - y_j) for every replica j, where y_j is the value after the
+// local step (held in x_j, or in the snapshot when the local step stored only that).
+// Table version: grid = chunks; the chunk of A is read once into registers and applied to all W
+// replicas: (8 + 4/W) bytes per replica-element.
 __device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
     v4f r;
     r.x = fmaf(om, a.x - x.x, x.x);
@@ -195,44 +236,70 @@ __device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
     return r;
 }
 
-template <bool NT>
+// FROM_S: the pre-merge value y is read from snapshot rows Y (row stride P_pad, chunk at foff)
+// instead of from x (the local step stored only the snapshot).
+template <bool FROM_S>
 __global__ void __launch_bounds__(kThreads)
 k_merge(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, const float *__restrict__ A,
-        int n_tensors, int W, float om)
+        const float *__restrict__ Y, int64_t P_pad, int n_tensors, int W, float om)
 {
     const Chunk c = chunks[blockIdx.x];
-    const float *__restrict__ a = A + c.foff;              // 256-byte aligned by construction
+    const float *__restrict__ a = A + c.foff;
     const v4f *a4 = reinterpret_cast<const v4f *>(a);
     const int tid = threadIdx.x;
     const int len = c.len;
     const bool full = (len == kChunk);
+    const bool a_aligned = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
 
     v4f ar[kUnroll];
-    if (full) {
+    if (full && a_aligned) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) ar[u] = ld4<NT>(a4 + tid + u * kThreads);
+        for (int u = 0; u < kUnroll; ++u) ar[u] = ld4<false>(a4 + tid + u * kThreads);
     }
     for (int j = 0; j < W; ++j) {
-        float *__restrict__ x = xp[(int64_t)j * n_tensors + c.tensor] + c.off;
-        const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+        float *x = xp[(int64_t)j * n_tensors + c.tensor] + c.off;
+        const float *y = FROM_S ? Y + (int64_t)j * P_pad + c.foff : x;
+        const bool aligned = a_aligned && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
         if (aligned) {
             v4f *x4 = reinterpret_cast<v4f *>(x);
+            const v4f *y4 = reinterpret_cast<const v4f *>(y);
             if (full) {
-                v4f xr[kUnroll];
+                v4f yr[kUnroll];
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) xr[u] = x4[tid + u * kThreads];
+                for (int u = 0; u < kUnroll; ++u) yr[u] = ld4<true>(y4 + tid + u * kThreads);
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) x4[tid + u * kThreads] = merge4(xr[u], ar[u], om);
+                for (int u = 0; u < kUnroll; ++u) st4<true>(x4 + tid + u * kThreads, merge4(yr[u], ar[u], om));
             } else {
                 const int n4 = len >> 2;
-                for (int i = tid; i < n4; i += kThreads) x4[i] = merge4(x4[i], a4[i], om);
+                for (int i = tid; i < n4; i += kThreads) x4[i] = merge4(y4[i], a4[i], om);
                 const int e = (n4 << 2) + tid;
-                if (e < len) { const float xs = x[e]; x[e] = fmaf(om, a[e] - xs, xs); }
+                if (e < len) { const float ys = y[e]; x[e] = fmaf(om, a[e] - ys, ys); }
             }
         } else {
-            for (int e = tid; e < len; e += kThreads) { const float xs = x[e]; x[e] = fmaf(om, a[e] - xs, xs); }
+            for (int e = tid; e < len; e += kThreads) { const float ys = y[e]; x[e] = fmaf(om, a[e] - ys, ys); }
         }
     }
+}
+
+// Matrix layout: X (and Y) are W rows of row4 128-bit columns, A is one row.  One wavefront handles
+// 64 columns of ONE replica; the workgroup index is decoded so that the W workgroups sharing a
+// piece of A run back to back on the same XCD (workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2): A is then fetched from HBM once and re-read from that L2 by the other W-1.
+template <int WT>   // WT > 0: W known at compile time; 0: any W
+__global__ void __launch_bounds__(kWave)
+k_merge_flat(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
+             int64_t n4, int64_t row4, int W, float om)
+{
+    const unsigned b = blockIdx.x;
+    const unsigned xcd = b & 7u, slot = b >> 3;
+    const unsigned w = WT > 0 ? (unsigned)WT : (unsigned)W;
+    const unsigned j = slot % w;
+    const int64_t piece = (int64_t)(slot / w) * 8 + xcd;
+    const int64_t i = piece * kWave + threadIdx.x;
+    if (i >= n4) return;
+    const v4f a = ld4<false>(A + i);
+    const v4f y = ld4<true>(Y + (int64_t)j * row4 + i);
+    st4<true>(X + (int64_t)j * row4 + i, merge4(y, a, om));
 }
 
 // ------------------------------------------------------------------------------------------------

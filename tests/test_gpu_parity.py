@@ -18,6 +18,10 @@ pytestmark = pytest.mark.gpu
 # one kernel pass: a handful of fp32 roundings (2^-24 each) on values up to ~5 rms of their tensor
 KERNEL_TOL = 2e-6
 RAGGED = [4096 * 3 + 5, 1000, 64, 1, 4096, 7, 2 * 4096 + 1023, 130]
+# the same plus two elements: the total becomes a multiple of 4, so flat arenas qualify as W x P
+# matrices (arithmetic addressing) while the tensors inside stay odd-sized and misaligned
+RAGGED4 = RAGGED + [2]
+SETS = {"table": RAGGED, "matrix": RAGGED4}
 
 
 def small(name="resnet50_w8", **kw):
@@ -36,12 +40,13 @@ def both_oracles(cfg, x_gpu, idx=None, steps=None):
 
 # ------------------------------------------------------------------------------------------------
 # single kernels
-@pytest.mark.parametrize("layout", ["arena", "separate"])
-def test_local_step_kernel(layout):
+@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table")])
+def test_local_step_kernel(layout, pset):
     """One local step (no averaging in reach) equals the oracle's local update, x and v."""
     import oracle
-    cfg = small(tau=1000, d=0, W=3, steps=3)
+    cfg = small(tau=1000, d=0, W=3, steps=3, params=custom_param_set(SETS[pset]))
     run = GpuRun(cfg, layout=layout)
+    assert (run.opt.layout()[1] == cfg.P) == (pset == "matrix")      # which addressing is in use
     x = run.weights().astype(np.float64); v = np.zeros_like(x)
     for k in range(3):
         run.step()
@@ -52,11 +57,12 @@ def test_local_step_kernel(layout):
     run.close()
 
 
+@pytest.mark.parametrize("pset", ["table", "matrix"])
 @pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 8, 12, 16, 17])
-def test_mean_kernel(W):
+def test_mean_kernel(W, pset):
     """The W-way mean of the snapshot equals the oracle's mean of the post-update weights."""
     import oracle
-    cfg = small(tau=1, d=3, W=W, steps=1)
+    cfg = small(tau=1, d=3, W=W, steps=1, params=custom_param_set(SETS[pset]))
     run = GpuRun(cfg)
     run.step()                                    # launches an average, merges nothing (d=3)
     y = run.weights()
@@ -68,11 +74,12 @@ def test_mean_kernel(W):
     run.close()
 
 
+@pytest.mark.parametrize("pset", ["table", "matrix"])
 @pytest.mark.parametrize("layout,xi", [("arena", 0.25), ("separate", 0.25), ("arena", 0.0), ("arena", 1.0)])
-def test_merge_kernel(layout, xi):
+def test_merge_kernel(layout, xi, pset):
     """A merge equals the oracle's merge of the same y and A; spread contracts by xi (Eq. 2)."""
     import oracle
-    cfg = small(tau=1, d=0, W=4, steps=1)
+    cfg = small(tau=1, d=0, W=4, steps=1, params=custom_param_set(SETS[pset]))
     # d=0: the step launches and merges at once; rebuild y from a twin run without merge (xi=1)
     y = run_gpu(cfg, steps=1, layout=layout, xi=1.0).astype(np.float64)
     got = run_gpu(cfg, steps=1, layout=layout, xi=xi)
@@ -87,9 +94,9 @@ def test_merge_kernel(layout, xi):
 # ------------------------------------------------------------------------------------------------
 # whole runs, small
 @pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 1, 4), (1, 2, 8), (4, 2, 16), (1, 4, 4), (3, 3, 5), (2, 5, 3), (5, 4, 2), (1, 2, 1)])
-@pytest.mark.parametrize("layout", ["arena", "separate"])
-def test_small_runs_match_oracle(tau, d, W, layout):
-    cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9)
+@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table")])
+def test_small_runs_match_oracle(tau, d, W, layout, pset):
+    cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
     both_oracles(cfg, run_gpu(cfg, layout=layout))
 
 
@@ -104,22 +111,25 @@ def test_every_step_matches_oracle_quadratic_small():
     assert max(errs) <= TOL
 
 
-def test_schedules_give_identical_results():
+@pytest.mark.parametrize("pset", ["table", "matrix"])
+def test_schedules_give_identical_results(pset):
     """Side-stream and single-stream schedules run the same kernels on the same data: bit-equal."""
     import paper_2006_00441_amd as pkg
-    cfg = small(tau=1, d=2, W=8, steps=20)
+    cfg = small(tau=1, d=2, W=8, steps=20, params=custom_param_set(SETS[pset]))
     a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP)
     b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL)
     assert np.array_equal(a, b)
 
 
-def test_learning_rate_and_gradient_table_changes():
+@pytest.mark.parametrize("pset", ["table", "matrix"])
+def test_learning_rate_and_gradient_table_changes(pset):
     """set_lr mid-run and a different set of gradient buffers every step (the pointer table is
-    re-uploaded through its rotation) against the oracle."""
+    re-uploaded through its rotation; every third buffer is not a W x P matrix, so the matrix
+    case alternates between arithmetic and table addressing) against the oracle."""
     import oracle
-    cfg = small(tau=2, d=1, W=4, steps=14)
+    cfg = small(tau=2, d=1, W=4, steps=14, params=custom_param_set(SETS[pset]))
     run = GpuRun(cfg)
-    alt = [torch.zeros_like(run.g_flat) for _ in range(6)]
+    alt = [torch.zeros(cfg.W, cfg.P + (8 if i % 3 == 2 else 0), device=run.dev)[:, :cfg.P] for i in range(6)]
     off = cfg.params.offsets
     w0 = wl.init_weights(cfg).numpy()
     ref = oracle.Oracle(cfg.W, cfg.P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, w0, xi=cfg.xi, dtype="f64")
@@ -132,6 +142,7 @@ def test_learning_rate_and_gradient_table_changes():
             buf.copy_(run.g_flat)
             run.g_flat.fill_(float("nan"))         # the library must read the table it was given
         ptrs = [buf[j, off[t]:off[t + 1]].data_ptr() for j in range(cfg.W) for t in range(cfg.params.n_tensors)]
+        assert ptrs[cfg.params.n_tensors] - ptrs[0] == 4 * (cfg.P + (8 if (k % len(alt)) % 3 == 2 else 0))
         run.opt.step(ptrs)
         ref.step(np.stack([wl.gradient(cfg, k, j).numpy() for j in range(cfg.W)]).astype(np.float64))
     assert max_scaled_error(cfg, run.weights(), ref.x) <= TOL
