@@ -30,6 +30,8 @@ def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
     return {"local_step": 20.0,                    # read x, v, g; write x, v
             "local_step_snapshot": 24.0,           # + write the snapshot
             "local_step_to_snapshot": 20.0,        # read x, v, g; write v and the snapshot (x is written by the merge)
+            "step_merge": 20.0 + 4.0 / W,          # local step with the merge folded in: + read the average
+            "step_snapshot_merge": 24.0 + 4.0 / W,  # ... + write the snapshot
             "mean": 4.0 + 4.0 / W,                 # read W snapshot rows, write one average
             "merge": 8.0 + 4.0 / W}[kernel]        # read x and the average (once), write x
 
@@ -106,10 +108,10 @@ class Bench:
         self.torch.cuda.empty_cache()
 
 
-def timed_region(cfg, steps: int, warmup: int):
+def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
     """The headline measurement: overlap schedule, per-kernel event timing live in the timed region."""
     import paper_2006_00441_amd as pkg
-    b = Bench(cfg, pkg.SCHED_OVERLAP)
+    b = Bench(cfg, pkg.SCHED_OVERLAP, gemm=gemm)
     for _ in range(warmup):
         b.step()
     b.opt.profile(True, 4 * steps + 16)
@@ -199,6 +201,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap-study", action="store_true")
     ap.add_argument("--only-timed", action="store_true", help="just the timed region (for profilers)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="first run 5 plain torch copies of W*P floats (a kernel of known traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the DaSGD pipeline on ONE GPU (W replicas share its HBM); "
@@ -215,7 +220,14 @@ def main() -> int:
     cfg = wl.get_config(args.workload)
     rp = cfg.W * cfg.P
 
-    wall, ev_ms, kernels = timed_region(cfg, args.steps, args.warmup)
+    if args.pmc_calibration:
+        src = torch.zeros(cfg.W, cfg.P, device="cuda:0"); dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+    wall, ev_ms, kernels = timed_region(cfg, args.steps, args.warmup, gemm=(cfg.name == "overlap"))
     ms_per_step = wall / args.steps * 1e3
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     for name, k in kernels.items():

@@ -59,6 +59,18 @@ enum {
                                 merge reads whatever the slot holds.  RESULTS ARE MEANINGLESS. */
 };
 
+/* How much of one iteration is fused into the local-step kernel (dasgd_set_fusion).  Results are the
+ * same at every level up to floating-point rounding of the same operations; only traffic differs. */
+enum {
+    DASGD_FUSE_NONE       = 0, /* the local step stores x, v (and the snapshot when an average follows);
+                                  the merge reads x, writes x */
+    DASGD_FUSE_SNAPSHOT   = 1, /* when a snapshot AND a merge fall on the same step, the local step stores
+                                  the new weights only into the snapshot and the merge reads them there */
+    DASGD_FUSE_STEP_MERGE = 2  /* default: when a merge is due at the step being taken (and d > 0), the local
+                                  step applies it in the same pass (Eq. 2, both branches at once) and
+                                  dasgd_merge only retires the average; otherwise as DASGD_FUSE_SNAPSHOT */
+};
+
 /* Kernels for dasgd_profile_read. */
 enum {
     DASGD_K_LOCAL_STEP         = 0, /* local step storing x, v                      (20 B per element) */
@@ -66,7 +78,9 @@ enum {
     DASGD_K_MEAN               = 2, /* W-way replica mean                            (4 + 4/W)         */
     DASGD_K_MERGE              = 3, /* delayed merge                                 (8 + 4/W)         */
     DASGD_K_LOCAL_STEP_TO_SNAP = 4, /* local step storing v and the snapshot only   (20 B per element) */
-    DASGD_K_COUNT              = 5
+    DASGD_K_STEP_MERGE         = 5, /* local step with the merge folded in          (20 + 4/W)        */
+    DASGD_K_STEP_SNAP_MERGE    = 6, /* ... that also stores the snapshot             (24 + 4/W)        */
+    DASGD_K_COUNT              = 7
 };
 
 /* Create a context for W replicas of P fp32 parameters each.
@@ -89,6 +103,9 @@ int dasgd_set_lr(dasgd_ctx *ctx, float lr);
 
 /* Choose the schedule (DASGD_SCHED_*).  Only legal while no average is pending. */
 int dasgd_set_schedule(dasgd_ctx *ctx, int schedule);
+
+/* Choose the fusion level (DASGD_FUSE_*).  Only legal while no average is pending. */
+int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
 
 /* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
  * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots
@@ -127,7 +144,10 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * dasgd_average_begin will launch.  When, in addition, a merge is due at this same step, the
  * kernel stores the new weights ONLY into the snapshot and dasgd_merge reads them from there:
  * x then holds the finished x_{k+1} only after this step's dasgd_merge (which the caller has to
- * issue before the next local step anyway).
+ * issue before the next local step anyway).  At the default fusion level a merge due at this step
+ * (d > 0) is applied by this same kernel, after a device-side wait for that average, with the xi
+ * in effect now; dasgd_merge then only retires the average.  In every case x holds x_{k+1} once
+ * the calls of the canonical loop for this step have been issued, and not necessarily before.
  *   g   [W * n_tensors] host array of device pointers (same order and shapes as x), read only;
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
  *       pointers of the previous call (the table is re-uploaded only when it changes).

@@ -21,6 +21,19 @@ constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
+// Multiplier and shift for fast_div by d (2 <= d < 2^31).
+FastDiv make_fast_div(unsigned d)
+{
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;                     // l = ceil(log2 d) >= 1
+    const unsigned long long m = ((1ull << (31 + l)) + d - 1) / d;
+    return FastDiv{(unsigned)m, l - 1};
+}
+
+// A is re-read once per replica; beyond this size it no longer stays in the 256 MB memory-side
+// cache between two re-reads a full row apart, and the XCD-local mapping is used instead.
+constexpr int64_t kRowsApartMaxBytes = 128ll << 20;
+
 struct Pending {
     int64_t launch_step;
     int slot;
@@ -46,6 +59,7 @@ struct dasgd_ctx {
     int64_t P = 0;
     float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
     int schedule = DASGD_SCHED_OVERLAP;
+    int fusion = DASGD_FUSE_STEP_MERGE;
     int slots = 1;
     // binding
     bool bound = false, dry = false;
@@ -67,11 +81,14 @@ struct dasgd_ctx {
     bool snap_valid = false;        // the latest local step stored a snapshot
     bool y_in_snap = false;         // ... and ONLY the snapshot: x is stale until this step's merge
     bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
+    bool merged_in_step = false;    // the latest local step already applied this step's merge
     int snap_slot = 0;
     // matrix layout: x, v (and g) are W x P row-major matrices, rows back to back, 16-byte aligned
     bool xv_matrix = false, g_matrix = false;
     float *x0 = nullptr, *v0 = nullptr;
     const float *g0 = nullptr;
+    bool idx32 = false;             // W*P/4 < 2^31: flat kernels may use 32-bit indices and fast division
+    FastDiv by_row = {0, 0};        // division by P/4
     std::deque<Pending> pending;
     std::vector<hipEvent_t> snap_done, avg_done;
     // profiling
@@ -256,6 +273,14 @@ int dasgd_set_schedule(dasgd_ctx *c, int schedule)
     return DASGD_OK;
 }
 
+int dasgd_set_fusion(dasgd_ctx *c, int fusion)
+{
+    if (!c || fusion < DASGD_FUSE_NONE || fusion > DASGD_FUSE_STEP_MERGE) return DASGD_EINVAL;
+    if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
+    c->fusion = fusion;
+    return DASGD_OK;
+}
+
 size_t dasgd_workspace_bytes(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 {
     if (!shapes_ok(c, n_tensors, numel)) return 0;
@@ -317,6 +342,8 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     c->xv_matrix = matrix;
     c->x0 = x[0];
     c->v0 = v[0];
+    c->idx32 = matrix && c->P >= 8 && (int64_t)c->W * c->P / 4 < (1ll << 31);
+    if (c->idx32) c->by_row = make_fast_div((unsigned)(c->P / 4));
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
@@ -380,8 +407,11 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     // will this very step end with a merge?  (d == 0: of the average it launches itself)
     const bool merge_follows = (c->d == 0) ? snap_step
                                            : (!c->pending.empty() && c->pending.front().launch_step == k - c->d);
+    const bool snap = snap_step && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
+    // fold the merge into this kernel?  (not for d == 0: that merge needs the mean of this step's own output)
+    const bool fold = merge_follows && c->d > 0 && c->fusion == DASGD_FUSE_STEP_MERGE;
     int mode = kStoreX;
-    if (snap_step && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) mode = merge_follows ? kStoreS : kStoreXS;
+    if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
     const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
 
     if (!c->dry) {
@@ -412,17 +442,33 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         }
         const int slot = (int)(c->n_launched % c->slots);
         float *S = mode == kStoreX ? nullptr : snap_ptr(c, slot);
-        const int kid = mode == kStoreX ? DASGD_K_LOCAL_STEP
+        const float *A = nullptr;
+        const float om = 1.0f - c->xi;
+        if (fold) {
+            const int aslot = c->pending.front().slot;
+            if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[aslot], 0));
+            A = avg_ptr(c, aslot);
+        }
+        const int kid = fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
+                      : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
         int rec;
         int rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        if (c->xv_matrix && c->g_matrix) {
+        const bool flat = c->xv_matrix && c->g_matrix && (!fold || c->idx32);
+        if (flat) {
             const int64_t n4 = (int64_t)c->W * c->P / 4;
             const dim3 grid((unsigned)((n4 + kWave - 1) / kWave));
             v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0), *s4 = reinterpret_cast<v4f *>(S);
             const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
-            if (mode == kStoreX)
+            if (fold) {
+                const v4f *A4 = reinterpret_cast<const v4f *>(A);
+                const unsigned row4 = (unsigned)(c->P / 4);
+                if (mode == kStoreX)
+                    hipLaunchKernelGGL((k_step_merge_flat<false>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4, (unsigned)n4, row4, c->by_row, c->lr, c->momentum, c->wd, om);
+                else
+                    hipLaunchKernelGGL((k_step_merge_flat<true>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4, (unsigned)n4, row4, c->by_row, c->lr, c->momentum, c->wd, om);
+            } else if (mode == kStoreX)
                 hipLaunchKernelGGL((k_local_step_flat<kStoreX>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
             else if (mode == kStoreXS)
                 hipLaunchKernelGGL((k_local_step_flat<kStoreXS>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
@@ -434,12 +480,15 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
             const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
             const dim3 grid((unsigned)c->lay.n_chunks, (unsigned)c->W);
-            if (mode == kStoreX)
-                hipLaunchKernelGGL((k_local_step<kStoreX>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
-            else if (mode == kStoreXS)
-                hipLaunchKernelGGL((k_local_step<kStoreXS>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
-            else
-                hipLaunchKernelGGL((k_local_step<kStoreS>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd);
+#define DASGD_LAUNCH_TABLE(MODE, MERGE)                                                                         \
+    hipLaunchKernelGGL((k_local_step<MODE, MERGE>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, \
+                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om)
+            if (fold && mode == kStoreX)       DASGD_LAUNCH_TABLE(kStoreX, true);
+            else if (fold)                     DASGD_LAUNCH_TABLE(kStoreXS, true);
+            else if (mode == kStoreX)          DASGD_LAUNCH_TABLE(kStoreX, false);
+            else if (mode == kStoreXS)         DASGD_LAUNCH_TABLE(kStoreXS, false);
+            else                               DASGD_LAUNCH_TABLE(kStoreS, false);
+#undef DASGD_LAUNCH_TABLE
         }
         HIPCHK(c, hipGetLastError());
         rc = prof_close(c, c->main_s, rec);
@@ -449,6 +498,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     c->begun_for_k = false;
     c->snap_valid = snap_step;
     c->y_in_snap = (mode == kStoreS);
+    c->merged_in_step = fold;
     c->mean_deferred = false;
     c->snap_slot = (int)(c->n_launched % c->slots);
     return DASGD_OK;
@@ -483,7 +533,7 @@ int dasgd_merge(dasgd_ctx *c)
     if (!c) return DASGD_EINVAL;
     if (!c->bound || !merge_due(c)) return DASGD_ESTATE;
     const int slot = c->pending.front().slot;
-    if (!c->dry) {
+    if (!c->dry && !c->merged_in_step) {
         if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
         const float *Y = c->y_in_snap ? snap_ptr(c, c->snap_slot) : nullptr;
         const float om = 1.0f - c->xi;
@@ -492,18 +542,24 @@ int dasgd_merge(dasgd_ctx *c)
         if (rc != DASGD_OK) return rc;
         if (c->xv_matrix) {
             const int64_t row4 = c->P / 4;
-            const int64_t pieces = (row4 + kWave - 1) / kWave;
-            const dim3 grid((unsigned)((pieces + 7) / 8 * 8 * c->W));
             v4f *X4 = reinterpret_cast<v4f *>(c->x0);
             const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
             const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
-            switch (c->W) {
-            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+            if (c->idx32 && c->P * 4 <= kRowsApartMaxBytes) {
+                const int64_t n4 = row4 * c->W;
+                hipLaunchKernelGGL(k_merge_flat_rows, dim3((unsigned)((n4 + kWave - 1) / kWave)), dim3(kWave), 0, c->main_s,
+                                   X4, Y4, A4, (unsigned)n4, (unsigned)row4, c->by_row, om);
+            } else {
+                const int64_t pieces = (row4 + kWave - 1) / kWave;
+                const dim3 grid((unsigned)((pieces + 7) / 8 * 8 * c->W));
+                switch (c->W) {
+                case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
+                }
             }
         } else {
             const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
@@ -517,13 +573,16 @@ int dasgd_merge(dasgd_ctx *c)
         HIPCHK(c, hipGetLastError());
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
+    }
+    if (!c->dry) {
         if (c->mean_deferred) {
-            rc = launch_average(c, c->snap_slot);
-            if (rc != DASGD_OK) return rc;
+            const int rc2 = launch_average(c, c->snap_slot);
+            if (rc2 != DASGD_OK) return rc2;
         }
     }
     c->mean_deferred = false;
     c->y_in_snap = false;
+    c->merged_in_step = false;
     c->pending.pop_front();
     return DASGD_OK;
 }

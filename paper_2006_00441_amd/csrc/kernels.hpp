@@ -73,16 +73,29 @@ __device__ __forceinline__ void sgd4(v4f &x, v4f &v, const v4f g, float lr, floa
     }
 }
 
+// Merge of one value: xi y + (1 - xi) a, computed as y + om (a - y) with om = 1 - xi  (Eq. 2, second branch).
+__device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
+    v4f r;
+    r.x = fmaf(om, a.x - x.x, x.x);
+    r.y = fmaf(om, a.y - x.y, x.y);
+    r.z = fmaf(om, a.z - x.z, x.z);
+    r.w = fmaf(om, a.w - x.w, x.w);
+    return r;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Local step on every replica through the chunk table: grid = (chunks, W).
 // 20 bytes per element (24 when both x and the snapshot are stored).
-template <int MODE>
+// MERGE: this step's merge is folded in -- the value stored to x is y + om (A - y), the snapshot
+// (if any) still receives y (paper Eq. 2, both branches in one pass).
+template <int MODE, bool MERGE>
 __global__ void __launch_bounds__(kThreads)
 k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, float *const *__restrict__ vp,
              const float *const *__restrict__ gp, float *__restrict__ S, int64_t P_pad, int n_tensors,
-             float lr, float momentum, float wd)
+             float lr, float momentum, float wd, const float *__restrict__ A, float om)
 {
     constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
+    static_assert(!(MERGE && MODE == kStoreS), "a folded merge always stores x");
     const Chunk c = chunks[blockIdx.x];
     const int j = blockIdx.y;
     const int64_t row = (int64_t)j * n_tensors + c.tensor;
@@ -90,32 +103,36 @@ k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, fl
     float *__restrict__ v = vp[row] + c.off;
     const float *__restrict__ g = gp[row] + c.off;
     float *__restrict__ s = WS ? S + (int64_t)j * P_pad + c.foff : nullptr;
+    const float *__restrict__ a = MERGE ? A + c.foff : nullptr;
     const int tid = threadIdx.x;
     const int len = c.len;
 
     const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(v) |
-                           reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(s)) & 15u) == 0;
+                           reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(s) |
+                           reinterpret_cast<uintptr_t>(a)) & 15u) == 0;
     if (aligned) {
         v4f *x4 = reinterpret_cast<v4f *>(x);
         v4f *v4 = reinterpret_cast<v4f *>(v);
         const v4f *g4 = reinterpret_cast<const v4f *>(g);
         v4f *s4 = reinterpret_cast<v4f *>(s);
+        const v4f *a4 = reinterpret_cast<const v4f *>(a);
         if (len == kChunk) {
-            v4f xr[kUnroll], vr[kUnroll], gr[kUnroll];
+            v4f xr[kUnroll], vr[kUnroll], gr[kUnroll], ar[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int i = tid + u * kThreads;
                 xr[u] = ld4<true>(x4 + i);
                 vr[u] = ld4<true>(v4 + i);
                 gr[u] = ld4<true>(g4 + i);
+                if (MERGE) ar[u] = ld4<false>(a4 + i);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int i = tid + u * kThreads;
                 sgd4(xr[u], vr[u], gr[u], lr, momentum, wd);
-                if (WX) st4<true>(x4 + i, xr[u]);
                 st4<true>(v4 + i, vr[u]);
                 if (WS) st4<true>(s4 + i, xr[u]);
+                if (WX) st4<true>(x4 + i, MERGE ? merge4(xr[u], ar[u], om) : xr[u]);
             }
         } else {
             const int n4 = len >> 2;
@@ -123,26 +140,26 @@ k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, fl
                 v4f xr = x4[i], vr = v4[i];
                 const v4f gr = g4[i];
                 sgd4(xr, vr, gr, lr, momentum, wd);
-                if (WX) x4[i] = xr;
                 v4[i] = vr;
                 if (WS) s4[i] = xr;
+                if (WX) x4[i] = MERGE ? merge4(xr, a4[i], om) : xr;
             }
             const int e = (n4 << 2) + tid;         // at most 3 leftover elements
             if (e < len) {
                 float xs = x[e], vs = v[e];
                 sgd1(xs, vs, g[e], lr, momentum, wd);
-                if (WX) x[e] = xs;
                 v[e] = vs;
                 if (WS) s[e] = xs;
+                if (WX) x[e] = MERGE ? fmaf(om, a[e] - xs, xs) : xs;
             }
         }
     } else {
         for (int e = tid; e < len; e += kThreads) {
             float xs = x[e], vs = v[e];
             sgd1(xs, vs, g[e], lr, momentum, wd);
-            if (WX) x[e] = xs;
             v[e] = vs;
             if (WS) s[e] = xs;
+            if (WX) x[e] = MERGE ? fmaf(om, a[e] - xs, xs) : xs;
         }
     }
 }
@@ -168,6 +185,53 @@ k_local_step_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restric
     if (WS) st4<true>(s + i, xr);
 }
 
+// Division of a 31-bit index by a fixed divisor d >= 2 as multiply-high and shift
+// (round-up method: mul = ceil(2^(31+l) / d), l = ceil(log2 d); exact for every n < 2^31).
+struct FastDiv {
+    unsigned mul, shift;
+};
+__device__ __forceinline__ unsigned fast_div(unsigned n, FastDiv f) { return __umulhi(n, f.mul) >> f.shift; }
+
+
+// Matrix layout, local step with this step's merge folded in (paper Eq. 2, both branches in one
+// pass): y = local update of x;  x <- y + (1 - xi)(A - y);  optionally snapshot <- y.
+// Reads x, v, g once and the average A once per replica (re-reads of A come from cache); writes
+// x, v [, snapshot]: 20 + 4/W bytes per replica-element (24 + 4/W with the snapshot) instead of the
+// 28 + 4/W (32 + 4/W) of separate local-step and merge kernels.  n4 = W*P/4 < 2^31.
+template <bool SNAP>
+__global__ void __launch_bounds__(kWave)
+k_step_merge_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
+                  const v4f *__restrict__ A, unsigned n4, unsigned row4, FastDiv by_row,
+                  float lr, float momentum, float wd, float om)
+{
+    const unsigned i = blockIdx.x * kWave + threadIdx.x;
+    if (i >= n4) return;
+    v4f xr = ld4<true>(x + i);
+    v4f vr = ld4<true>(v + i);
+    const v4f gr = ld4<true>(g + i);
+    const unsigned c = i - fast_div(i, by_row) * row4;        // column inside the replica's row
+    const v4f a = ld4<false>(A + c);
+    sgd4(xr, vr, gr, lr, momentum, wd);
+    st4<true>(v + i, vr);
+    if (SNAP) st4<true>(s + i, xr);
+    st4<true>(x + i, merge4(xr, a, om));
+}
+
+// Matrix layout merge addressed by the flat index (every access of x and y is a whole aligned
+// kilobyte per wavefront whatever the row length); the W re-reads of A are a full row apart, so this
+// mapping is chosen when A fits the memory-side cache.  n4 = W*P/4 < 2^31.
+__global__ void __launch_bounds__(kWave)
+k_merge_flat_rows(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
+                  unsigned n4, unsigned row4, FastDiv by_row, float om)
+{
+    const unsigned i = blockIdx.x * kWave + threadIdx.x;
+    if (i >= n4) return;
+    const unsigned c = i - fast_div(i, by_row) * row4;
+    const v4f a = ld4<false>(A + c);
+    const v4f y = ld4<true>(Y + i);
+    st4<true>(X + i, merge4(y, a, om));
+}
+
 // ------------------------------------------------------------------------------------------------
 // Sum of r[LO..HI) in pairwise (tree) order.
 template <int LO, int HI> __device__ __forceinline__ v4f tree_sum(const v4f *r) {
@@ -186,6 +250,9 @@ template <int WT, int U, bool NT>
 __global__ void __launch_bounds__(kWave)
 k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4, int W, float inv_w)
 {
+    // The mean runs beside whatever the caller has on the main stream (typically dense compute that
+    // leaves wave slots free but keeps the issue ports busy): its few instructions go first.
+    __builtin_amdgcn_s_setprio(3);
     const int64_t base = (int64_t)blockIdx.x * (kWave * U) + threadIdx.x;
     if constexpr (WT > 0) {
         v4f r[U][WT];
@@ -227,14 +294,6 @@ k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4,
 // local step (held in x_j, or in the snapshot when the local step stored only that).
 // Table version: grid = chunks; the chunk of A is read once into registers and applied to all W
 // replicas: (8 + 4/W) bytes per replica-element.
-__device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
-    v4f r;
-    r.x = fmaf(om, a.x - x.x, x.x);
-    r.y = fmaf(om, a.y - x.y, x.y);
-    r.z = fmaf(om, a.z - x.z, x.z);
-    r.w = fmaf(om, a.w - x.w, x.w);
-    return r;
-}
 
 // FROM_S: the pre-merge value y is read from snapshot rows Y (row stride P_pad, chunk at foff)
 // instead of from x (the local step stored only the snapshot).

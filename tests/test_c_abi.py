@@ -54,6 +54,11 @@ def test_create_validates_arguments():
         o.set_lr(float("inf"))
     with pytest.raises(DasgdError):
         o.set_schedule(7)
+    for f in (-1, 3):
+        with pytest.raises(DasgdError):
+            o.set_fusion(f)
+    for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE):
+        o.set_fusion(f)
     o.destroy()
 
 

@@ -100,6 +100,18 @@ def test_small_runs_match_oracle(tau, d, W, layout, pset):
     both_oracles(cfg, run_gpu(cfg, layout=layout))
 
 
+@pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 2, 8), (4, 2, 16), (2, 4, 3), (3, 3, 5)])
+@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table")])
+def test_fusion_levels_agree_bit_for_bit(tau, d, W, layout, pset):
+    """Separate kernels, merge-from-snapshot and merge-folded-into-the-local-step do the same
+    operations on the same values in the same order: identical bits; and they match the oracle."""
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
+    runs = [run_gpu(cfg, layout=layout, fusion=f) for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE)]
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+    both_oracles(cfg, runs[0])
+
+
 def test_every_step_matches_oracle_quadratic_small():
     """Quadratic workload (gradients depend on the current weights): checked after every step."""
     cfg = wl.get_config("quadratic").scaled(params=wl.flat_param_set(3 * 4096 + 77))
@@ -111,13 +123,14 @@ def test_every_step_matches_oracle_quadratic_small():
     assert max(errs) <= TOL
 
 
+@pytest.mark.parametrize("fusion", [0, 1, 2])
 @pytest.mark.parametrize("pset", ["table", "matrix"])
-def test_schedules_give_identical_results(pset):
+def test_schedules_give_identical_results(pset, fusion):
     """Side-stream and single-stream schedules run the same kernels on the same data: bit-equal."""
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=8, steps=20, params=custom_param_set(SETS[pset]))
-    a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP)
-    b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL)
+    a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion)
+    b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion)
     assert np.array_equal(a, b)
 
 
@@ -179,8 +192,9 @@ def test_config_quadratic_full_every_step():
     both_oracles(cfg, run_gpu(cfg))
 
 
-@pytest.mark.parametrize("name", ["resnet50_w8", "resnet50_w16", "bert_large_w4"])
-def test_config_full_size_sampled(name):
+@pytest.mark.parametrize("name,fusion", [("resnet50_w8", 2), ("resnet50_w8", 1), ("resnet50_w8", 0),
+                                         ("resnet50_w16", 2), ("bert_large_w4", 2), ("bert_large_w4", 1)])
+def test_config_full_size_sampled(name, fusion):
     """Full-size run in the launch configuration the benchmark times; compared on sampled
     coordinates (all small tensors entirely, chunk boundaries, heads, tails, random elements):
     the method is elementwise across coordinates, so the oracle runs on exactly those."""
@@ -196,7 +210,7 @@ def test_config_full_size_sampled(name):
         if (k + 1) in checkpoints:
             errs[k + 1] = max_scaled_error(cfg, r.weights(idx), ref[k + 1], idx)
             print(f"[{name}] after step {k + 1}: scaled error {errs[k + 1]:.2e}", flush=True)
-    x_gpu = run_gpu(cfg, observer=obs, idx=idx)
+    x_gpu = run_gpu(cfg, observer=obs, idx=idx, fusion=fusion)
     assert max(errs.values()) <= TOL
     e32 = max_scaled_error(cfg, x_gpu, run_oracle(cfg, "f32", idx=idx), idx)
     print(f"[{name}] final vs f32 oracle {e32:.2e} on {idx.numel()} sampled coordinates", flush=True)
