@@ -52,11 +52,17 @@ enum {
 
 /* Schedules (dasgd_set_schedule).  All use the same kernels. */
 enum {
-    DASGD_SCHED_OVERLAP = 0, /* default: the W-way mean runs on the side stream, event-ordered
-                                (the paper's point: averaging hidden behind d local steps) */
+    DASGD_SCHED_OVERLAP = 0, /* default: the W-way mean runs on the side stream, event-ordered, beside
+                                whatever the caller enqueues on the main stream after this step's calls
+                                (the next forward/backward pass -- the paper's point: averaging hidden
+                                behind local work, Fig. 2 and Fig. 4).  The library's own kernels, which
+                                all saturate HBM, wait for a mean in flight instead of competing with it */
     DASGD_SCHED_SERIAL  = 1, /* everything on the main stream in program order (no overlap) */
-    DASGD_SCHED_NO_AVERAGE_TIMING_ONLY = 2 /* timing floor: no snapshot and no mean are run, the
+    DASGD_SCHED_NO_AVERAGE_TIMING_ONLY = 2, /* timing floor: no snapshot and no mean are run, the
                                 merge reads whatever the slot holds.  RESULTS ARE MEANINGLESS. */
+    DASGD_SCHED_OVERLAP_FREE = 3 /* side-stream mean with the full d local steps of slack: main-stream
+                                kernels wait only for the average they read, so a mean may also run
+                                beside the library's own local steps and merges */
 };
 
 /* How much of one iteration is fused into the local-step kernel (dasgd_set_fusion).  Results are the
@@ -190,13 +196,15 @@ int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
  * main_stream in the serial schedule) has drained.  EINVAL if which is out of range. */
 int dasgd_pending_average(const dasgd_ctx *ctx, int which, int64_t *launch_step, size_t *byte_offset);
 
-/* Per-kernel timing.  enable != 0: bracket every kernel launch with timing events on its own
- * stream (at most max_records launches are recorded; later ones run untimed).  enable == 0: stop. */
-int dasgd_profile(dasgd_ctx *ctx, int enable, int max_records);
+/* Per-kernel timing.  every_n >= 1: bracket one launch in every_n of each kernel kind with timing
+ * events on its own stream (at most max_records launches are recorded; later ones run untimed);
+ * every_n == 0: stop.  An event pair costs a few microseconds on the stream, hence the sampling. */
+int dasgd_profile(dasgd_ctx *ctx, int every_n, int max_records);
 
-/* Wait for both streams, then return the summed duration and the number of recorded launches of
- * kernel `kernel` (DASGD_K_*) since profiling was enabled or last read, and reset them. */
-int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *launches);
+/* Wait for both streams, then return, for kernel `kernel` (DASGD_K_*) since profiling was enabled
+ * or last read: the summed duration of the timed launches, how many were timed, and how many were
+ * launched in all; then reset the three.  Any output pointer may be NULL. */
+int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *timed, int64_t *launched);
 
 /* HIP error code of the most recent DASGD_EHIP (0 if none). */
 int dasgd_last_hip_error(const dasgd_ctx *ctx);

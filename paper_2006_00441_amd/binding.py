@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence, Tuple
 from . import build as _build
 
 DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
-SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY = 0, 1, 2
+SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY, SCHED_OVERLAP_FREE = 0, 1, 2, 3
 K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, K_LOCAL_STEP_TO_SNAP, K_STEP_MERGE, K_STEP_SNAP_MERGE = 0, 1, 2, 3, 4, 5, 6
 FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE = 0, 1, 2
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
@@ -47,7 +47,7 @@ EXPORTS = {
     "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64]),
     "dasgd_pending_average": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, ctypes.POINTER(ctypes.c_size_t)]),
     "dasgd_profile": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
-    "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64]),
+    "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64, _pi64]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
 }
@@ -187,14 +187,17 @@ class DaSGD:
                     self._lib.dasgd_pending_average(self._h, int(which), ctypes.byref(ls), ctypes.byref(bo)))
         return int(ls.value), int(bo.value)
 
-    def profile(self, enable: bool, max_records: int = 4096) -> None:
-        self._check("dasgd_profile", self._lib.dasgd_profile(self._h, 1 if enable else 0, int(max_records)))
+    def profile(self, every_n: int, max_records: int = 4096) -> None:
+        """Time one launch in every_n of each kernel kind (0 = off)."""
+        self._check("dasgd_profile", self._lib.dasgd_profile(self._h, int(every_n), int(max_records)))
 
-    def profile_read(self, kernel: int) -> Tuple[float, int]:
-        """(total milliseconds, launches) of one kernel since enabled / last read; blocks."""
-        ms = ctypes.c_double(); n = ctypes.c_int64()
-        self._check("dasgd_profile_read", self._lib.dasgd_profile_read(self._h, int(kernel), ctypes.byref(ms), ctypes.byref(n)))
-        return float(ms.value), int(n.value)
+    def profile_read(self, kernel: int) -> Tuple[float, int, int]:
+        """(milliseconds summed over the timed launches, timed launches, all launches) of one kernel
+        since profiling was enabled / last read; blocks until both streams have drained."""
+        ms = ctypes.c_double(); n = ctypes.c_int64(); m = ctypes.c_int64()
+        self._check("dasgd_profile_read", self._lib.dasgd_profile_read(self._h, int(kernel), ctypes.byref(ms),
+                                                                       ctypes.byref(n), ctypes.byref(m)))
+        return float(ms.value), int(n.value), int(m.value)
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

@@ -21,22 +21,10 @@ constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
-// Multiplier and shift for fast_div by d (2 <= d < 2^31).
-FastDiv make_fast_div(unsigned d)
-{
-    unsigned l = 0;
-    while ((1ull << l) < d) ++l;                     // l = ceil(log2 d) >= 1
-    const unsigned long long m = ((1ull << (31 + l)) + d - 1) / d;
-    return FastDiv{(unsigned)m, l - 1};
-}
-
-// A is re-read once per replica; beyond this size it no longer stays in the 256 MB memory-side
-// cache between two re-reads a full row apart, and the XCD-local mapping is used instead.
-constexpr int64_t kRowsApartMaxBytes = 128ll << 20;
-
 struct Pending {
     int64_t launch_step;
     int slot;
+    bool awaited;       // the main stream already waits for this average's mean kernel
 };
 
 struct ProfRec {
@@ -87,13 +75,14 @@ struct dasgd_ctx {
     bool xv_matrix = false, g_matrix = false;
     float *x0 = nullptr, *v0 = nullptr;
     const float *g0 = nullptr;
-    bool idx32 = false;             // W*P/4 < 2^31: flat kernels may use 32-bit indices and fast division
-    FastDiv by_row = {0, 0};        // division by P/4
+    bool idx32 = false;             // 64 <= P/4 and W*P/4 + 64 < 2^31: the column-aware flat kernels apply
+                                    // (32-bit indices; a 64-element block spans at most two rows)
     std::deque<Pending> pending;
     std::vector<hipEvent_t> snap_done, avg_done;
     // profiling
-    bool prof = false;
+    int prof_every = 0;             // 0: off; n: time one launch in n of every kernel kind
     int prof_max = 0;
+    int64_t prof_seen[DASGD_K_COUNT] = {};
     std::vector<ProfRec> prof_recs;
     std::vector<ProfRec> prof_pool;
     int last_hip = 0;
@@ -178,6 +167,11 @@ inline float *avg_ptr(const dasgd_ctx *c, int slot)
     return reinterpret_cast<float *>(c->ws + c->lay.A) + (size_t)slot * (size_t)c->lay.P_pad;
 }
 
+inline bool side_stream_mean(const dasgd_ctx *c)
+{
+    return c->schedule == DASGD_SCHED_OVERLAP || c->schedule == DASGD_SCHED_OVERLAP_FREE;
+}
+
 inline bool begin_due(const dasgd_ctx *c)
 {
     return c->n_done > 0 && (c->n_done % c->tau) == 0 && !c->begun_for_k;     // (k+1) mod tau == 0
@@ -191,7 +185,8 @@ inline bool merge_due(const dasgd_ctx *c)
 int prof_open(dasgd_ctx *c, int kernel, hipStream_t s, int *rec_index)
 {
     *rec_index = -1;
-    if (!c->prof || (int)c->prof_recs.size() >= c->prof_max) return DASGD_OK;
+    if (c->prof_every <= 0) return DASGD_OK;
+    if ((c->prof_seen[kernel]++ % c->prof_every) != 0 || (int)c->prof_recs.size() >= c->prof_max) return DASGD_OK;
     ProfRec r;
     if (!c->prof_pool.empty()) {
         r = c->prof_pool.back();
@@ -219,7 +214,7 @@ int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A)
     const v4f *S4 = reinterpret_cast<const v4f *>(S);
     v4f *A4 = reinterpret_cast<v4f *>(A);
     const float inv_w = 1.0f / (float)c->W;
-    auto grid = [&](int U) { return dim3((unsigned)((n4 + (int64_t)kWave * U - 1) / ((int64_t)kWave * U))); };
+    auto grid = [&](int U) { return dim3((unsigned)(((n4 + (int64_t)kWave * U - 1) / ((int64_t)kWave * U) + 63) / 64 * 64)); };
     switch (c->W) {
     case 1:  hipLaunchKernelGGL((k_mean<1, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
     case 2:  hipLaunchKernelGGL((k_mean<2, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
@@ -267,7 +262,7 @@ int dasgd_set_lr(dasgd_ctx *c, float lr)
 
 int dasgd_set_schedule(dasgd_ctx *c, int schedule)
 {
-    if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) return DASGD_EINVAL;
+    if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_OVERLAP_FREE) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->schedule = schedule;
     return DASGD_OK;
@@ -342,8 +337,7 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     c->xv_matrix = matrix;
     c->x0 = x[0];
     c->v0 = v[0];
-    c->idx32 = matrix && c->P >= 8 && (int64_t)c->W * c->P / 4 < (1ll << 31);
-    if (c->idx32) c->by_row = make_fast_div((unsigned)(c->P / 4));
+    c->idx32 = matrix && c->P / 4 >= 64 && (int64_t)c->W * c->P / 4 + 64 < (1ll << 31) && (int64_t)decode_grid((unsigned)c->W, (unsigned)(c->P / 4)) < (1ll << 31);
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
@@ -380,7 +374,7 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
 static int launch_average(dasgd_ctx *c, int slot)
 {
     hipStream_t s = c->main_s;
-    if (c->schedule == DASGD_SCHED_OVERLAP) {
+    if (side_stream_mean(c)) {
         HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
         HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
         s = c->side_s;
@@ -392,7 +386,7 @@ static int launch_average(dasgd_ctx *c, int slot)
     if (rc != DASGD_OK) return rc;
     rc = prof_close(c, s, rec);
     if (rc != DASGD_OK) return rc;
-    if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
+    if (side_stream_mean(c)) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
     return DASGD_OK;
 }
 
@@ -444,11 +438,20 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         float *S = mode == kStoreX ? nullptr : snap_ptr(c, slot);
         const float *A = nullptr;
         const float om = 1.0f - c->xi;
-        if (fold) {
-            const int aslot = c->pending.front().slot;
-            if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[aslot], 0));
-            A = avg_ptr(c, aslot);
+        // Default overlap schedule: every kernel of this library saturates HBM, so letting a mean run
+        // beside one only makes both slower; the local step therefore waits for the means in flight,
+        // which leaves them whatever the caller put on the main stream since the last merge (the
+        // forward/backward pass) to hide behind.  The free variant waits only for the average it reads.
+        if (side_stream_mean(c)) {
+            for (size_t p = 0; p < c->pending.size(); ++p) {
+                Pending &pe = c->pending[p];
+                const bool needed = fold && p == 0;
+                if (pe.awaited || !(needed || c->schedule == DASGD_SCHED_OVERLAP)) continue;
+                HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[pe.slot], 0));
+                pe.awaited = true;
+            }
         }
+        if (fold) A = avg_ptr(c, c->pending.front().slot);
         const int kid = fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
@@ -464,10 +467,22 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             if (fold) {
                 const v4f *A4 = reinterpret_cast<const v4f *>(A);
                 const unsigned row4 = (unsigned)(c->P / 4);
-                if (mode == kStoreX)
-                    hipLaunchKernelGGL((k_step_merge_flat<false>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4, (unsigned)n4, row4, c->by_row, c->lr, c->momentum, c->wd, om);
-                else
-                    hipLaunchKernelGGL((k_step_merge_flat<true>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4, (unsigned)n4, row4, c->by_row, c->lr, c->momentum, c->wd, om);
+                const dim3 fgrid(decode_grid((unsigned)c->W, row4));
+#define DASGD_LAUNCH_FOLD(SNAP, WT)                                                                             \
+    hipLaunchKernelGGL((k_step_merge_flat<SNAP, WT>), fgrid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4,     \
+                       (unsigned)n4, row4, c->W, c->lr, c->momentum, c->wd, om)
+#define DASGD_LAUNCH_FOLD_W(SNAP)                                                                               \
+    switch (c->W) {                                                                                             \
+    case 1:  DASGD_LAUNCH_FOLD(SNAP, 1);  break;                                                                \
+    case 2:  DASGD_LAUNCH_FOLD(SNAP, 2);  break;                                                                \
+    case 4:  DASGD_LAUNCH_FOLD(SNAP, 4);  break;                                                                \
+    case 8:  DASGD_LAUNCH_FOLD(SNAP, 8);  break;                                                                \
+    case 16: DASGD_LAUNCH_FOLD(SNAP, 16); break;                                                                \
+    default: DASGD_LAUNCH_FOLD(SNAP, 0);  break;                                                                \
+    }
+                if (mode == kStoreX) { DASGD_LAUNCH_FOLD_W(false) } else { DASGD_LAUNCH_FOLD_W(true) }
+#undef DASGD_LAUNCH_FOLD_W
+#undef DASGD_LAUNCH_FOLD
             } else if (mode == kStoreX)
                 hipLaunchKernelGGL((k_local_step_flat<kStoreX>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
             else if (mode == kStoreXS)
@@ -522,7 +537,7 @@ int dasgd_average_begin(dasgd_ctx *c)
             if (rc != DASGD_OK) return rc;
         }
     }
-    c->pending.push_back(Pending{c->n_done - 1, slot});
+    c->pending.push_back(Pending{c->n_done - 1, slot, false});
     c->n_launched += 1;
     c->begun_for_k = true;
     return DASGD_OK;
@@ -534,32 +549,26 @@ int dasgd_merge(dasgd_ctx *c)
     if (!c->bound || !merge_due(c)) return DASGD_ESTATE;
     const int slot = c->pending.front().slot;
     if (!c->dry && !c->merged_in_step) {
-        if (c->schedule == DASGD_SCHED_OVERLAP) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
+        if (side_stream_mean(c) && !c->pending.front().awaited) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
         const float *Y = c->y_in_snap ? snap_ptr(c, c->snap_slot) : nullptr;
         const float om = 1.0f - c->xi;
         int rec;
         int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        if (c->xv_matrix) {
+        if (c->xv_matrix && c->idx32) {
             const int64_t row4 = c->P / 4;
             v4f *X4 = reinterpret_cast<v4f *>(c->x0);
             const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
             const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
-            if (c->idx32 && c->P * 4 <= kRowsApartMaxBytes) {
-                const int64_t n4 = row4 * c->W;
-                hipLaunchKernelGGL(k_merge_flat_rows, dim3((unsigned)((n4 + kWave - 1) / kWave)), dim3(kWave), 0, c->main_s,
-                                   X4, Y4, A4, (unsigned)n4, (unsigned)row4, c->by_row, om);
-            } else {
-                const int64_t pieces = (row4 + kWave - 1) / kWave;
-                const dim3 grid((unsigned)((pieces + 7) / 8 * 8 * c->W));
-                switch (c->W) {
-                case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, row4, row4, c->W, om); break;
-                }
+            const unsigned n4 = (unsigned)(row4 * c->W);
+            const dim3 grid(decode_grid((unsigned)c->W, (unsigned)row4));
+            switch (c->W) {
+            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
             }
         } else {
             const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
@@ -617,16 +626,17 @@ int dasgd_pending_average(const dasgd_ctx *c, int which, int64_t *launch_step, s
     return DASGD_OK;
 }
 
-int dasgd_profile(dasgd_ctx *c, int enable, int max_records)
+int dasgd_profile(dasgd_ctx *c, int every_n, int max_records)
 {
-    if (!c || (enable && max_records < 1)) return DASGD_EINVAL;
+    if (!c || every_n < 0 || (every_n > 0 && max_records < 1)) return DASGD_EINVAL;
     if (!c->bound || c->dry) return DASGD_ESTATE;
-    c->prof = enable != 0;
-    c->prof_max = enable ? max_records : 0;
+    c->prof_every = every_n;
+    c->prof_max = every_n > 0 ? max_records : 0;
+    for (int k = 0; k < DASGD_K_COUNT; ++k) c->prof_seen[k] = 0;
     return DASGD_OK;
 }
 
-int dasgd_profile_read(dasgd_ctx *c, int kernel, double *total_ms, int64_t *launches)
+int dasgd_profile_read(dasgd_ctx *c, int kernel, double *total_ms, int64_t *timed, int64_t *launched)
 {
     if (!c || kernel < 0 || kernel >= DASGD_K_COUNT) return DASGD_EINVAL;
     if (!c->bound || c->dry) return DASGD_ESTATE;
@@ -645,7 +655,9 @@ int dasgd_profile_read(dasgd_ctx *c, int kernel, double *total_ms, int64_t *laun
     }
     c->prof_recs.swap(keep);
     if (total_ms) *total_ms = sum;
-    if (launches) *launches = n;
+    if (timed) *timed = n;
+    if (launched) *launched = c->prof_seen[kernel];
+    c->prof_seen[kernel] = 0;
     return DASGD_OK;
 }
 

@@ -185,51 +185,58 @@ k_local_step_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restric
     if (WS) st4<true>(s + i, xr);
 }
 
-// Division of a 31-bit index by a fixed divisor d >= 2 as multiply-high and shift
-// (round-up method: mul = ceil(2^(31+l) / d), l = ceil(log2 d); exact for every n < 2^31).
-struct FastDiv {
-    unsigned mul, shift;
-};
-__device__ __forceinline__ unsigned fast_div(unsigned n, FastDiv f) { return __umulhi(n, f.mul) >> f.shift; }
-
+// Work decomposition of the matrix-layout kernels that need the column of an element (to read the
+// average A): the flat index space [0, W*row4) of 128-bit elements is cut into aligned blocks of 64
+// (one wavefront, one whole kilobyte per array whatever the row length -- misaligned kilobytes cost
+// 15 % of the bandwidth on MI355X).  Blocks are issued grouped by column window, the W replicas of a
+// window back to back on ONE XCD (workgroups are dealt round-robin to the 8 XCDs, each with its own
+// L2): the window of A is fetched from HBM once and re-read from that L2 by the other W-1 replicas.
+// A block that holds the boundary between rows j and j+1 belongs to row j and serves both.
+// Returns false if this workgroup/lane has nothing to do; else the flat index i and the column c.
+__device__ __forceinline__ bool decode_block(unsigned b, unsigned W, unsigned row4, unsigned n4,
+                                             unsigned &i, unsigned &c)
+{
+    const unsigned xcd = b & 7u, slot = b >> 3;
+    const unsigned j = slot % W;
+    const unsigned q = (slot / W) * 8u + xcd;                // column window
+    const unsigned lo = j * row4, hi = lo + row4;            // flat range of row j
+    const unsigned first = j ? (lo >> 6) + 1u : 0u;          // first block owned by row j
+    const unsigned last = (j == W - 1u) ? ((n4 - 1u) >> 6) : (hi >> 6);
+    const unsigned blk = first + q;
+    if (blk > last) return false;
+    i = blk * kWave + threadIdx.x;
+    if (i >= n4) return false;
+    c = (i >= hi) ? i - hi : i - lo;
+    return true;
+}
+// Number of workgroups decode_block needs.
+static inline unsigned decode_grid(unsigned W, unsigned row4)
+{
+    const unsigned windows = (row4 >> 6) + 2u;               // blocks one row can own, upper bound
+    return (windows + 7u) / 8u * 8u * W;
+}
 
 // Matrix layout, local step with this step's merge folded in (paper Eq. 2, both branches in one
 // pass): y = local update of x;  x <- y + (1 - xi)(A - y);  optionally snapshot <- y.
-// Reads x, v, g once and the average A once per replica (re-reads of A come from cache); writes
-// x, v [, snapshot]: 20 + 4/W bytes per replica-element (24 + 4/W with the snapshot) instead of the
-// 28 + 4/W (32 + 4/W) of separate local-step and merge kernels.  n4 = W*P/4 < 2^31.
-template <bool SNAP>
+// Reads x, v, g once and the average A once (re-reads come from L2); writes x, v [, snapshot]:
+// 20 + 4/W bytes per replica-element (24 + 4/W with the snapshot) instead of the 28 + 4/W (32 + 4/W)
+// of separate local-step and merge kernels.  Needs n4 = W*P/4 < 2^31.
+template <bool SNAP, int WT>   // WT > 0: W known at compile time; 0: any W
 __global__ void __launch_bounds__(kWave)
 k_step_merge_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
-                  const v4f *__restrict__ A, unsigned n4, unsigned row4, FastDiv by_row,
+                  const v4f *__restrict__ A, unsigned n4, unsigned row4, int W,
                   float lr, float momentum, float wd, float om)
 {
-    const unsigned i = blockIdx.x * kWave + threadIdx.x;
-    if (i >= n4) return;
+    unsigned i, c;
+    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, i, c)) return;
     v4f xr = ld4<true>(x + i);
     v4f vr = ld4<true>(v + i);
     const v4f gr = ld4<true>(g + i);
-    const unsigned c = i - fast_div(i, by_row) * row4;        // column inside the replica's row
     const v4f a = ld4<false>(A + c);
     sgd4(xr, vr, gr, lr, momentum, wd);
     st4<true>(v + i, vr);
     if (SNAP) st4<true>(s + i, xr);
     st4<true>(x + i, merge4(xr, a, om));
-}
-
-// Matrix layout merge addressed by the flat index (every access of x and y is a whole aligned
-// kilobyte per wavefront whatever the row length); the W re-reads of A are a full row apart, so this
-// mapping is chosen when A fits the memory-side cache.  n4 = W*P/4 < 2^31.
-__global__ void __launch_bounds__(kWave)
-k_merge_flat_rows(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
-                  unsigned n4, unsigned row4, FastDiv by_row, float om)
-{
-    const unsigned i = blockIdx.x * kWave + threadIdx.x;
-    if (i >= n4) return;
-    const unsigned c = i - fast_div(i, by_row) * row4;
-    const v4f a = ld4<false>(A + c);
-    const v4f y = ld4<true>(Y + i);
-    st4<true>(X + i, merge4(y, a, om));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -253,7 +260,11 @@ k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4,
     // The mean runs beside whatever the caller has on the main stream (typically dense compute that
     // leaves wave slots free but keeps the issue ports busy): its few instructions go first.
     __builtin_amdgcn_s_setprio(3);
-    const int64_t base = (int64_t)blockIdx.x * (kWave * U) + threadIdx.x;
+    // Eight consecutive 64-column windows go to the same XCD back to back: when the rows are not
+    // 128-byte aligned relative to each other, the cache line two neighbouring windows share is
+    // then found in that XCD's L2 instead of being fetched from HBM twice.
+    const int64_t blk = ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7);
+    const int64_t base = blk * (kWave * U) + threadIdx.x;
     if constexpr (WT > 0) {
         v4f r[U][WT];
 #pragma unroll
@@ -340,25 +351,19 @@ k_merge(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, const f
     }
 }
 
-// Matrix layout: X (and Y) are W rows of row4 128-bit columns, A is one row.  One wavefront handles
-// 64 columns of ONE replica; the workgroup index is decoded so that the W workgroups sharing a
-// piece of A run back to back on the same XCD (workgroups are dealt round-robin to the 8 XCDs, each
-// with its own L2): A is then fetched from HBM once and re-read from that L2 by the other W-1.
+// Matrix layout merge: X (and Y, the values after the local step: X itself or the snapshot) are W
+// rows of row4 128-bit columns back to back, A is one row.  Same decomposition as the folded kernel.
+// (8 + 4/W) bytes per replica-element.  Needs n4 = W*P/4 < 2^31.
 template <int WT>   // WT > 0: W known at compile time; 0: any W
 __global__ void __launch_bounds__(kWave)
 k_merge_flat(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
-             int64_t n4, int64_t row4, int W, float om)
+             unsigned n4, unsigned row4, int W, float om)
 {
-    const unsigned b = blockIdx.x;
-    const unsigned xcd = b & 7u, slot = b >> 3;
-    const unsigned w = WT > 0 ? (unsigned)WT : (unsigned)W;
-    const unsigned j = slot % w;
-    const int64_t piece = (int64_t)(slot / w) * 8 + xcd;
-    const int64_t i = piece * kWave + threadIdx.x;
-    if (i >= n4) return;
-    const v4f a = ld4<false>(A + i);
-    const v4f y = ld4<true>(Y + (int64_t)j * row4 + i);
-    st4<true>(X + (int64_t)j * row4 + i, merge4(y, a, om));
+    unsigned i, c;
+    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, i, c)) return;
+    const v4f a = ld4<false>(A + c);
+    const v4f y = ld4<true>(Y + i);
+    st4<true>(X + i, merge4(y, a, om));
 }
 
 // ------------------------------------------------------------------------------------------------

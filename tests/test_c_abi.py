@@ -146,5 +146,5 @@ def test_gpu_calls_fail_loudly_without_a_device():
     with pytest.raises(RuntimeError):
         o.bind_tensors([[torch.zeros(4)]], [[torch.zeros(4)]], None, None)
     with pytest.raises(DasgdError):
-        o.profile(True)
+        o.profile(1)
     o.destroy()

@@ -21,7 +21,9 @@ RAGGED = [4096 * 3 + 5, 1000, 64, 1, 4096, 7, 2 * 4096 + 1023, 130]
 # the same plus two elements: the total becomes a multiple of 4, so flat arenas qualify as W x P
 # matrices (arithmetic addressing) while the tensors inside stay odd-sized and misaligned
 RAGGED4 = RAGGED + [2]
-SETS = {"table": RAGGED, "matrix": RAGGED4}
+SETS = {"table": RAGGED, "matrix": RAGGED4,
+        "matrix_tiny": [100, 24],              # W x P matrix whose rows are shorter than one 64-wide block
+        "matrix_even": [4096, 256 * 7, 256]}   # rows that are a whole number of 64-wide blocks
 
 
 def small(name="resnet50_w8", **kw):
@@ -101,7 +103,8 @@ def test_small_runs_match_oracle(tau, d, W, layout, pset):
 
 
 @pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 2, 8), (4, 2, 16), (2, 4, 3), (3, 3, 5)])
-@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table")])
+@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table"),
+                                         ("arena", "matrix_tiny"), ("arena", "matrix_even")])
 def test_fusion_levels_agree_bit_for_bit(tau, d, W, layout, pset):
     """Separate kernels, merge-from-snapshot and merge-folded-into-the-local-step do the same
     operations on the same values in the same order: identical bits; and they match the oracle."""
@@ -131,7 +134,8 @@ def test_schedules_give_identical_results(pset, fusion):
     cfg = small(tau=1, d=2, W=8, steps=20, params=custom_param_set(SETS[pset]))
     a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion)
     b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion)
-    assert np.array_equal(a, b)
+    c = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP_FREE, fusion=fusion)
+    assert np.array_equal(a, b) and np.array_equal(a, c)
 
 
 @pytest.mark.parametrize("pset", ["table", "matrix"])
