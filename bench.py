@@ -147,6 +147,48 @@ def overlap_study(cfg, steps: int, warmup: int, gemm: bool):
             "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4)}
 
 
+def compare_algorithms(cfg, steps: int, warmup: int):
+    """The paper's three update schedules (Fig. 4; Eq. 4-6) timed on the same kernels, each local step
+    preceded by the forward/backward stand-in (one bf16 8192^3 GEMM): synchronous Mini-batch SGD
+    (blocking gradient mean every step, Eq. 1), Local SGD (tau = 4, blocking weight average, i.e.
+    d = 0, xi = 0) and DaSGD (tau = 4, d = 2, xi = 0.25, the paper's parameter-study baseline), against a
+    floor with local steps only.  share = (T - T_floor) / T, the on-device counterpart of the
+    communication shares the paper simulates (Section 5.2)."""
+    import torch
+    import paper_2006_00441_amd as pkg
+    variants = {
+        "local_steps_only": dict(tau=10 ** 9, d=0, xi=1.0, mb=False),
+        "minibatch_sgd": dict(tau=10 ** 9, d=0, xi=1.0, mb=True),
+        "local_sgd_tau4": dict(tau=4, d=0, xi=0.0, mb=False),
+        "dasgd_tau4_d2": dict(tau=4, d=2, xi=0.25, mb=False),
+        "dasgd_tau1_d2": dict(tau=1, d=2, xi=0.25, mb=False),
+    }
+    out = {}
+    for name, v in variants.items():
+        c = cfg.scaled(tau=min(v["tau"], 2 ** 30), d=v["d"], xi=v["xi"])
+        b = Bench(c, pkg.SCHED_OVERLAP, gemm=True)
+        if v["mb"]:
+            gbar = torch.zeros(c.P, device="cuda:0")
+            off = c.params.offsets
+            bcast = [gbar[off[t]:off[t + 1]].data_ptr() for _ in range(c.W) for t in range(c.params.n_tensors)]
+            G = b.g.data_ptr()
+
+            def step(b=b, gbar=gbar, bcast=bcast, G=G):
+                with torch.cuda.stream(b.main):
+                    torch.matmul(b.ga, b.gb, out=b.gc)
+                b.opt.gradient_average(G, gbar.data_ptr())
+                b.opt.step(bcast if b.first else None)
+                b.first = False
+            b.step = step
+        best = min(b.run(steps, warmup if r == 0 else 2)[0] for r in range(3))
+        out[name] = best / steps * 1e3
+        b.close()
+    floor = out["local_steps_only"]
+    return {"ms_per_step": {k: round(t, 4) for k, t in out.items()},
+            "averaging_share": {k: round((t - floor) / t, 4) for k, t in out.items() if k != "local_steps_only"},
+            "note": "each step = bf16 8192^3 GEMM stand-in + the schedule's parameter work, W=%d replicas" % cfg.W}
+
+
 def cpu_baseline(cfg, budget_s: float = 12.0):
     """The CPU oracle (fp32 variant, as it stands) timed on this machine's host cores on a bounded number
     of steps of the same workload at full size."""
@@ -266,6 +308,8 @@ def main() -> int:
         k = max(20, min(args.steps, 100))
         out["overlap"] = {"hbm_bound_steps_only": overlap_study(cfg, k, 10, gemm=False),
                           "with_compute_stand_in": overlap_study(cfg, k, 10, gemm=True)}
+        if cfg.kind == "external" and cfg.P % 4 == 0:
+            out["algorithms"] = compare_algorithms(cfg, 40, 8)
     if not args.only_timed and not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

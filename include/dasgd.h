@@ -180,6 +180,27 @@ int dasgd_average_begin(dasgd_ctx *ctx);
  * ESTATE: no pending average, or the oldest one was not launched at step k - d. */
 int dasgd_merge(dasgd_ctx *ctx);
 
+/* One whole iteration of Eq. 2, the canonical loop in a single call:
+ *     dasgd_local_step(ctx, g); if begin due: dasgd_average_begin(ctx); if merge due: dasgd_merge(ctx);
+ * *began / *merged (may be NULL) tell whether an average was launched / retired.  Errors as the three
+ * calls; on an error of the second or third call the earlier ones have taken effect. */
+int dasgd_step(dasgd_ctx *ctx, const float *const *g, int *began, int *merged);
+
+/* Mean over the replicas of a W x P row-major matrix of gradients, out[i] = (1/W) sum_j G[j*P + i], on
+ * main_stream with the W-way mean kernel: the reduction step of synchronous Mini-batch SGD in its
+ * per-worker form, x_{k+1} = x_k - (eta/M) sum_j g_j (Section 2.1, Eq. 1), provided so that the
+ * paper's comparison schedules (Mini-batch SGD, Local SGD as d = 0) can be timed on the same kernels.
+ *   G    device, W*P floats, rows back to back, 16-byte aligned, read only;  P must be a multiple of 4
+ *   out  device, P floats, 16-byte aligned; may then be passed as every replica's gradient
+ * EINVAL: null / misaligned pointer or P % 4 != 0.  ESTATE: not bound. */
+int dasgd_gradient_average(dasgd_ctx *ctx, const float *G, float *out);
+
+/* The paper's guideline for the delay (Section 3.4, Eq. 3: the communication must fit into d local
+ * iterations, t_c < d t_p) and for the period (Section 6.4: tau = d + 1): returns the smallest integer
+ * d >= 1 with t_c < d * t_p, and tau = d + 1.  t_c: time of one weight averaging (>= 0), t_p: time of
+ * one local iteration (> 0), any common unit.  Host-only.  EINVAL on non-finite or out-of-range input. */
+int dasgd_choose_delay(double t_c, double t_p, int *d, int *tau);
+
 /* Report the state: k (index of the last completed local step, -1 before the first), number of
  * pending averages, and whether dasgd_average_begin / dasgd_merge are due now.  Any output
  * pointer may be NULL. */

@@ -43,6 +43,9 @@ EXPORTS = {
     "dasgd_local_step": (ctypes.c_int, [_vp, _pp]),
     "dasgd_average_begin": (ctypes.c_int, [_vp]),
     "dasgd_merge": (ctypes.c_int, [_vp]),
+    "dasgd_step": (ctypes.c_int, [_vp, _pp, _pint, _pint]),
+    "dasgd_gradient_average": (ctypes.c_int, [_vp, _vp, _vp]),
+    "dasgd_choose_delay": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, _pint, _pint]),
     "dasgd_query": (ctypes.c_int, [_vp, _pi64, _pint, _pint, _pint]),
     "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64]),
     "dasgd_pending_average": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, ctypes.POINTER(ctypes.c_size_t)]),
@@ -87,6 +90,15 @@ def lib() -> ctypes.CDLL:
         f.argtypes = args
     _LIB = L
     return L
+
+
+def choose_delay(t_c: float, t_p: float) -> Tuple[int, int]:
+    """(d, tau) by the paper's guideline (dasgd_choose_delay)."""
+    d = ctypes.c_int(); tau = ctypes.c_int()
+    rc = lib().dasgd_choose_delay(float(t_c), float(t_p), ctypes.byref(d), ctypes.byref(tau))
+    if rc < 0:
+        raise DasgdError("dasgd_choose_delay", rc)
+    return int(d.value), int(tau.value)
 
 
 def _ptr_array(ptrs: Sequence[int]):
@@ -160,6 +172,11 @@ class DaSGD:
             arr = _ptr_array(g_ptrs)
         self._check("dasgd_local_step", self._lib.dasgd_local_step(self._h, arr))
 
+    def gradient_average(self, G_ptr: int, out_ptr: int) -> None:
+        """out = mean over the W rows of the W x P gradient matrix at G_ptr (dasgd_gradient_average)."""
+        self._check("dasgd_gradient_average",
+                    self._lib.dasgd_gradient_average(self._h, ctypes.c_void_p(int(G_ptr)), ctypes.c_void_p(int(out_ptr))))
+
     def average_begin(self) -> None:
         self._check("dasgd_average_begin", self._lib.dasgd_average_begin(self._h))
 
@@ -211,17 +228,18 @@ class DaSGD:
         except Exception:
             pass
 
-    # -- the canonical iteration (the caller loop of the header, for convenience) ------------------
     def step(self, g_ptrs: Optional[Sequence[int]] = None) -> Tuple[bool, bool]:
-        """local_step, then average_begin / merge when due.  Returns (began, merged)."""
-        self.local_step(g_ptrs)
-        _, _, b, _ = self.query()
-        if b:
-            self.average_begin()
-        _, _, _, m = self.query()
-        if m:
-            self.merge()
-        return b, m
+        """One whole iteration (dasgd_step): local_step, then average_begin / merge when due.
+        Returns (began, merged)."""
+        if g_ptrs is None:
+            arr = None
+        else:
+            if len(g_ptrs) != self.W * self.n_tensors:
+                raise DasgdError("dasgd_step", DASGD_EINVAL)
+            arr = _ptr_array(g_ptrs)
+        b = ctypes.c_int(); m = ctypes.c_int()
+        self._check("dasgd_step", self._lib.dasgd_step(self._h, arr, ctypes.byref(b), ctypes.byref(m)))
+        return bool(b.value), bool(m.value)
 
     # -- torch marshalling -------------------------------------------------------------------------
     def bind_tensors(self, x: Sequence[Sequence["torch.Tensor"]], v: Sequence[Sequence["torch.Tensor"]],

@@ -208,9 +208,9 @@ int prof_close(dasgd_ctx *c, hipStream_t s, int rec_index)
     return DASGD_OK;
 }
 
-int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A)
+int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A, int64_t row_elems)
 {
-    const int64_t n4 = c->lay.P_pad / 4;
+    const int64_t n4 = row_elems / 4;
     const v4f *S4 = reinterpret_cast<const v4f *>(S);
     v4f *A4 = reinterpret_cast<v4f *>(A);
     const float inv_w = 1.0f / (float)c->W;
@@ -382,7 +382,7 @@ static int launch_average(dasgd_ctx *c, int slot)
     int rec;
     int rc = prof_open(c, DASGD_K_MEAN, s, &rec);
     if (rc != DASGD_OK) return rc;
-    rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot));
+    rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot), c->lay.P_pad);
     if (rc != DASGD_OK) return rc;
     rc = prof_close(c, s, rec);
     if (rc != DASGD_OK) return rc;
@@ -593,6 +593,50 @@ int dasgd_merge(dasgd_ctx *c)
     c->y_in_snap = false;
     c->merged_in_step = false;
     c->pending.pop_front();
+    return DASGD_OK;
+}
+
+int dasgd_step(dasgd_ctx *c, const float *const *g, int *began, int *merged)
+{
+    if (began) *began = 0;
+    if (merged) *merged = 0;
+    int rc = dasgd_local_step(c, g);
+    if (rc != DASGD_OK) return rc;
+    if (begin_due(c)) {
+        rc = dasgd_average_begin(c);
+        if (rc != DASGD_OK) return rc;
+        if (began) *began = 1;
+    }
+    if (merge_due(c)) {
+        rc = dasgd_merge(c);
+        if (rc != DASGD_OK) return rc;
+        if (merged) *merged = 1;
+    }
+    return DASGD_OK;
+}
+
+int dasgd_gradient_average(dasgd_ctx *c, const float *G, float *out)
+{
+    if (!c || !G || !out) return DASGD_EINVAL;
+    if (!c->bound || c->dry) return DASGD_ESTATE;
+    if (c->P % 4 != 0) return DASGD_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(out)) & 15u) return DASGD_EINVAL;
+    int rec;
+    int rc = prof_open(c, DASGD_K_MEAN, c->main_s, &rec);
+    if (rc != DASGD_OK) return rc;
+    rc = launch_mean(c, c->main_s, G, out, c->P);
+    if (rc != DASGD_OK) return rc;
+    return prof_close(c, c->main_s, rec);
+}
+
+int dasgd_choose_delay(double t_c, double t_p, int *d, int *tau)
+{
+    if (!(t_c >= 0.0) || !(t_p > 0.0) || !std::isfinite(t_c) || !std::isfinite(t_p)) return DASGD_EINVAL;
+    const double r = std::floor(t_c / t_p);
+    if (r > 1.0e6) return DASGD_EINVAL;
+    const int dd = (int)r + 1;              // smallest integer d with t_c < d * t_p
+    if (d) *d = dd;
+    if (tau) *tau = dd + 1;
     return DASGD_OK;
 }
 

@@ -148,3 +148,37 @@ def test_gpu_calls_fail_loudly_without_a_device():
     with pytest.raises(DasgdError):
         o.profile(1)
     o.destroy()
+
+
+def test_choose_delay_reproduces_table_2():
+    """The delay / period guideline (Section 3.4 Eq. 3, Section 6.4) gives the paper's own choices for
+    all 14 cells of Table 2 (tests/golden/table2_delay.txt)."""
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "table2_delay.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 14
+    for model, cluster, t_p, t_c, d, tau in rows:
+        assert pkg.choose_delay(float(t_c), float(t_p)) == (int(d), int(tau)), (model, cluster)
+    assert pkg.choose_delay(0.0, 1.0) == (1, 2)
+    assert pkg.choose_delay(2.0, 1.0) == (3, 4)          # t_c < d t_p is strict
+    for bad in ((-1.0, 1.0), (1.0, 0.0), (float("nan"), 1.0), (1.0, float("inf"))):
+        with pytest.raises(DasgdError):
+            pkg.choose_delay(*bad)
+
+
+def test_step_is_the_canonical_loop():
+    """dasgd_step == local_step + average_begin when due + merge when due (dry run: state only)."""
+    for tau, d in ((1, 2), (4, 2), (3, 0)):
+        a = DaSGD(2, 8, d, tau, 0.1, 0.9, 0.0); a.bind_dry_run([8])
+        b = DaSGD(2, 8, d, tau, 0.1, 0.9, 0.0); b.bind_dry_run([8])
+        for k in range(5 * tau + d + 2):
+            began, merged = a.step(None)
+            b.local_step(None)
+            _, _, bd, _ = b.query()
+            if bd:
+                b.average_begin()
+            _, _, _, md = b.query()
+            if md:
+                b.merge()
+            assert (began, merged) == (bd, md)
+            assert a.query() == b.query()
+        a.destroy(); b.destroy()

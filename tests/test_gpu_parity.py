@@ -236,3 +236,27 @@ def test_replicas_contract_at_full_size():
     for j in range(1, cfg.W):
         assert torch.equal(run.x_flat[j], run.x_flat[0])
     run.close()
+
+
+def test_minibatch_sgd_on_the_same_kernels():
+    """Mini-batch SGD in per-worker form (Section 2.1, Eq. 1): the gradient mean by
+    dasgd_gradient_average, then every replica steps with it.  All replicas stay identical and
+    equal (a) the oracle run with d=0, tau=1, xi=0 (synchronous averaging of the weights, which is
+    the same trajectory) and (b) the library's own d=0, tau=1, xi=0 run."""
+    import oracle
+    base = small(tau=1000, d=0, W=4, steps=12, params=custom_param_set(SETS["matrix"]))
+    run = GpuRun(base)
+    gbar = torch.zeros(base.P, device=run.dev)
+    off = base.params.offsets
+    bcast = [gbar[off[t]:off[t + 1]].data_ptr() for _ in range(base.W) for t in range(base.params.n_tensors)]
+    for k in range(base.steps):
+        run.fill_gradients(k)
+        run.opt.gradient_average(run.g_flat.data_ptr(), gbar.data_ptr())
+        run.opt.step(bcast)
+    x_mb = run.weights()
+    run.close()
+    for j in range(1, base.W):
+        assert np.array_equal(x_mb[j], x_mb[0])
+    sync = base.scaled(tau=1, d=0, xi=0.0)
+    assert max_scaled_error(base, x_mb, run_oracle(sync, "f64")) <= TOL
+    assert max_scaled_error(base, x_mb, run_gpu(sync)) <= TOL
