@@ -40,6 +40,9 @@ def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
 class Bench:
     """Device state for one workload: W replicas of (x, v, g) in flat arenas plus a bound context."""
 
+    fusion = None
+    layout = "matrix"      # "matrix": W x P arenas (arithmetic addressing); "separate": one allocation per tensor
+
     def __init__(self, cfg, schedule: int, gemm: bool = False):
         import torch
         import workloads as wl
@@ -70,11 +73,23 @@ class Bench:
                 self.gc = torch.empty(8192, 8192, device=dev, dtype=torch.bfloat16)
                 del ii
         self.gemm = gemm
-        view = lambda a: [[a[j, off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
+        if Bench.layout == "separate":      # every tensor its own allocation: the multi-tensor (chunk table) path
+            view = lambda a: [[a[j, off[t]:off[t + 1]].clone() for t in range(n)] for j in range(W)]
+        else:
+            view = lambda a: [[a[j, off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
         self.opt = pkg.DaSGD(W, P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, xi=cfg.xi)
-        self.ws = self.opt.bind_tensors(view(self.x), view(self.v), self.main, self.side)
+        with torch.cuda.stream(self.main):
+            xs, vs, gs = view(self.x), view(self.v), view(self.g)
+        self.main.synchronize()
+        if Bench.layout == "separate":
+            self.x = self.v = self.g = None
+            torch.cuda.empty_cache()
+        self._tensors = (xs, vs, gs)
+        self.ws = self.opt.bind_tensors(xs, vs, self.main, self.side)
         self.opt.set_schedule(schedule)
-        self.g_ptrs = pkg.DaSGD.grad_pointers(view(self.g))
+        if Bench.fusion is not None:
+            self.opt.set_fusion(Bench.fusion)
+        self.g_ptrs = pkg.DaSGD.grad_pointers(gs)
         self.first = True
         self.main.synchronize()
 
@@ -103,7 +118,7 @@ class Bench:
 
     def close(self):
         self.opt.destroy()
-        for a in ("x", "v", "g", "ws", "ga", "gb", "gc"):
+        for a in ("x", "v", "g", "ws", "ga", "gb", "gc", "_tensors"):
             if hasattr(self, a):
                 delattr(self, a)
         self.torch.cuda.empty_cache()
@@ -246,6 +261,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap-study", action="store_true")
     ap.add_argument("--only-timed", action="store_true", help="just the timed region (for profilers)")
+    ap.add_argument("--layout", default="matrix", choices=["matrix", "separate"],
+                    help="matrix: x, v, g as W x P arenas (default); separate: one allocation per tensor")
+    ap.add_argument("--fusion", type=int, default=None, help="fusion level 0..2 (default: the library's)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run 5 plain torch copies of W*P floats (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -262,6 +280,8 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU implementation of this path", file=sys.stderr)
         return 2
     pkg.lib()
+    Bench.layout = args.layout
+    Bench.fusion = args.fusion
     cfg = wl.get_config(args.workload)
     rp = cfg.W * cfg.P
 
@@ -292,7 +312,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.params.name}-shaped, {cfg.params.n_tensors} fp32 tensors, "
                                f"P={cfg.P}, W={cfg.W}, tau={cfg.tau}, d={cfg.d}, xi={cfg.xi}",
-                   "schedule": "overlap (mean on side stream)", "replica_params": rp},
+                   "schedule": "overlap (mean on side stream)", "layout": args.layout, "replica_params": rp},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac_of_hbm_peak"], "avg_ms": d["avg_ms"], "launches": d["launches"], "timed_launches": d["timed_launches"],
                      "algorithmic_bytes_per_launch": d["algorithmic_bytes"],
@@ -308,7 +328,7 @@ def main() -> int:
         k = max(20, min(args.steps, 100))
         out["overlap"] = {"hbm_bound_steps_only": overlap_study(cfg, k, 10, gemm=False),
                           "with_compute_stand_in": overlap_study(cfg, k, 10, gemm=True)}
-        if cfg.kind == "external" and cfg.P % 4 == 0:
+        if cfg.kind == "external" and cfg.P % 4 == 0 and args.layout == "matrix":
             out["algorithms"] = compare_algorithms(cfg, 40, 8)
     if not args.only_timed and not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

@@ -260,3 +260,91 @@ def test_minibatch_sgd_on_the_same_kernels():
     sync = base.scaled(tau=1, d=0, xi=0.0)
     assert max_scaled_error(base, x_mb, run_oracle(sync, "f64")) <= TOL
     assert max_scaled_error(base, x_mb, run_gpu(sync)) <= TOL
+
+
+# ------------------------------------------------------------------------------------------------
+# parameter ranges the paper studies (Section 4.3: xi, delay, local steps) with a one-cycle
+# learning-rate schedule (Section 4.1) driven through dasgd_set_lr, on the quadratic workload
+def one_cycle(k, K, lo=0.01, hi=0.1):
+    up = int(0.3 * K)
+    return lo + (hi - lo) * k / up if k < up else hi - (hi - lo) * (k - up) / max(K - up, 1)
+
+
+@pytest.mark.parametrize("xi", [0.0, 0.25, 0.6, 1.0])
+@pytest.mark.parametrize("tau,d", [(1, 0), (1, 1), (1, 3), (2, 1), (4, 2), (4, 3), (4, 7), (8, 2)])
+def test_parameter_sweep_quadratic(xi, tau, d):
+    import oracle
+    cfg = wl.get_config("quadratic").scaled(params=wl.flat_param_set(2 * 4096 + 8), tau=tau, d=d, xi=xi, steps=30)
+    run = GpuRun(cfg)
+    q = wl.QuadraticProblem.build(cfg, "cpu")
+    ref = oracle.Oracle(cfg.W, cfg.P, d, tau, cfg.lr, cfg.momentum, cfg.wd, np.zeros(cfg.P), xi=xi, dtype="f64")
+    for k in range(cfg.steps):
+        lr = one_cycle(k, cfg.steps)
+        run.opt.set_lr(lr); ref.set_lr(lr)
+        run.step()
+        ref.step(np.stack([q.grad(torch.from_numpy(ref.x[j]), k, j).numpy() for j in range(cfg.W)]))
+    assert max_scaled_error(cfg, run.weights(), ref.x) <= TOL
+    run.close(); ref.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# argument checking that needs a device
+def test_bind_rejects_bad_arguments():
+    import paper_2006_00441_amd as pkg
+    dev = torch.device("cuda:0")
+    P, W = 1024, 2
+    x = [[torch.zeros(P, device=dev)] for _ in range(W)]
+    v = [[torch.zeros(P, device=dev)] for _ in range(W)]
+    m, s = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    xp = [t.data_ptr() for r in x for t in r]; vp = [t.data_ptr() for r in v for t in r]
+
+    def fresh():
+        return pkg.DaSGD(W, P, 1, 1, 0.1, 0.9, 0.0)
+
+    o = fresh()
+    need = o.workspace_bytes([P])
+    ws = torch.empty(need + 512, dtype=torch.uint8, device=dev)
+
+    def code(f):
+        with pytest.raises(pkg.DasgdError) as e:
+            f()
+        return e.value.code
+
+    assert code(lambda: o.bind([P], xp, vp, ws.data_ptr(), need - 1, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_ENOMEM
+    assert code(lambda: o.bind([P], xp, vp, ws.data_ptr() + 4, need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P], xp, vp, ws.data_ptr(), need, m.cuda_stream, m.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P], [0] + xp[1:], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P], [xp[0] + 2] + xp[1:], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P - 1], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    o.bind([P], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)
+    assert code(lambda: o.bind([P], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_ESTATE
+    assert code(lambda: o.local_step(None)) == pkg.DASGD_EINVAL            # no gradient table yet
+    assert code(lambda: o.local_step([0, 0])) == pkg.DASGD_EINVAL          # null gradient pointers
+    assert o.query()[0] == -1                                              # nothing ran
+    g = [[torch.zeros(P, device=dev)] for _ in range(W)]
+    o.step([t.data_ptr() for r in g for t in r])
+    assert o.query()[0] == 0
+    o.destroy()
+
+
+@pytest.mark.parametrize("W", [32, 64])
+def test_many_replicas(W):
+    cfg = small(tau=2, d=3, W=W, steps=11, params=custom_param_set([4096 + 12, 300]))
+    both_oracles(cfg, run_gpu(cfg))
+
+
+def test_profile_counts_and_times_launches():
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=1, d=2, W=8, steps=12, params=custom_param_set(SETS["matrix"]))
+    run = GpuRun(cfg)
+    run.opt.profile(2, 100)
+    for _ in range(cfg.steps):
+        run.step()
+    total = 0
+    for kid, name in pkg.KERNEL_NAMES.items():
+        ms, timed, launched = run.opt.profile_read(kid)
+        assert timed == (launched + 1) // 2 and (ms > 0) == (timed > 0)
+        total += launched
+    assert total == 2 * cfg.steps                                          # one step kernel + one mean per step
+    run.opt.profile(0)
+    run.close()
