@@ -33,6 +33,8 @@ def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
             "local_step_to_snapshot": 20.0,        # read x, v, g; write v and the snapshot (x is written by the merge)
             "step_merge": 20.0 + 4.0 / W,          # local step with the merge folded in: + read the average
             "step_snapshot_merge": 24.0 + 4.0 / W,  # ... + write the snapshot
+            "step_mean": 20.0 + 4.0 / W,           # local step that also writes the mean
+            "step_mean_merge": 20.0 + 8.0 / W,     # local step, mean and merge in one pass
             "mean": 4.0 + 4.0 / W,                 # read W snapshot rows, write one average
             "merge": 8.0 + 4.0 / W}[kernel]        # read x and the average (once), write x
 
@@ -41,7 +43,8 @@ class Bench:
     """Device state for one workload: W replicas of (x, v, g) in flat arenas plus a bound context."""
 
     fusion = None
-    layout = "matrix"      # "matrix": W x P arenas (arithmetic addressing); "separate": one allocation per tensor
+    layout = "matrix"      # "matrix": W x P arenas, rows 128-byte aligned (arithmetic addressing);
+                           # "separate": one allocation per tensor (chunk-table addressing)
 
     def __init__(self, cfg, schedule: int, gemm: bool = False):
         import torch
@@ -53,11 +56,12 @@ class Bench:
         self.side = torch.cuda.Stream(dev)
         W, P = cfg.W, cfg.P
         off, n = cfg.params.offsets, cfg.params.n_tensors
+        ld = (P + 31) // 32 * 32            # row stride: rows 128-byte aligned to each other
         with torch.cuda.stream(self.main):
             w0 = wl.init_weights(cfg, dev)
-            self.x = w0.unsqueeze(0).repeat(W, 1).contiguous()
-            self.v = torch.zeros(W, P, device=dev)
-            self.g = torch.empty(W, P, device=dev)
+            self._full = [torch.zeros(W, ld, device=dev) for _ in range(3)]
+            self.x, self.v, self.g = (a[:, :P] for a in self._full)
+            self.x.copy_(w0.unsqueeze(0).expand(W, P))
             if cfg.kind == "external":
                 sigma = wl.grad_sigma_vector(cfg, dev)
                 for j in range(W):
@@ -82,7 +86,7 @@ class Bench:
             xs, vs, gs = view(self.x), view(self.v), view(self.g)
         self.main.synchronize()
         if Bench.layout == "separate":
-            self.x = self.v = self.g = None
+            self.x = self.v = self.g = self._full = None
             torch.cuda.empty_cache()
         self._tensors = (xs, vs, gs)
         self.ws = self.opt.bind_tensors(xs, vs, self.main, self.side)
@@ -118,7 +122,7 @@ class Bench:
 
     def close(self):
         self.opt.destroy()
-        for a in ("x", "v", "g", "ws", "ga", "gb", "gc", "_tensors"):
+        for a in ("x", "v", "g", "_full", "ws", "ga", "gb", "gc", "_tensors"):
             if hasattr(self, a):
                 delattr(self, a)
         self.torch.cuda.empty_cache()
@@ -186,12 +190,14 @@ def compare_algorithms(cfg, steps: int, warmup: int):
             gbar = torch.zeros(c.P, device="cuda:0")
             off = c.params.offsets
             bcast = [gbar[off[t]:off[t + 1]].data_ptr() for _ in range(c.W) for t in range(c.params.n_tensors)]
-            G = b.g.data_ptr()
+            G = torch.zeros(c.W, c.P, device="cuda:0")      # gradient_average wants rows back to back
+            G.copy_(b.g)
+            Gp = G.data_ptr()
 
-            def step(b=b, gbar=gbar, bcast=bcast, G=G):
+            def step(b=b, gbar=gbar, bcast=bcast, Gp=Gp):
                 with torch.cuda.stream(b.main):
                     torch.matmul(b.ga, b.gb, out=b.gc)
-                b.opt.gradient_average(G, gbar.data_ptr())
+                b.opt.gradient_average(Gp, gbar.data_ptr())
                 b.opt.step(bcast if b.first else None)
                 b.first = False
             b.step = step
@@ -263,7 +269,7 @@ def main() -> int:
     ap.add_argument("--only-timed", action="store_true", help="just the timed region (for profilers)")
     ap.add_argument("--layout", default="matrix", choices=["matrix", "separate"],
                     help="matrix: x, v, g as W x P arenas (default); separate: one allocation per tensor")
-    ap.add_argument("--fusion", type=int, default=None, help="fusion level 0..2 (default: the library's)")
+    ap.add_argument("--fusion", type=int, default=None, help="fusion level 0..3 (default: the library's)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run 5 plain torch copies of W*P floats (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")

@@ -72,9 +72,15 @@ enum {
                                   the merge reads x, writes x */
     DASGD_FUSE_SNAPSHOT   = 1, /* when a snapshot AND a merge fall on the same step, the local step stores
                                   the new weights only into the snapshot and the merge reads them there */
-    DASGD_FUSE_STEP_MERGE = 2  /* default: when a merge is due at the step being taken (and d > 0), the local
+    DASGD_FUSE_STEP_MERGE = 2, /* default: when a merge is due at the step being taken (and d > 0), the local
                                   step applies it in the same pass (Eq. 2, both branches at once) and
                                   dasgd_merge only retires the average; otherwise as DASGD_FUSE_SNAPSHOT */
+    DASGD_FUSE_ALL        = 3  /* the mean is computed by the local-step kernel too (one lane updates one
+                                  column of all W replicas): no snapshot, no mean kernel, nothing on the
+                                  side stream; dasgd_average_begin and dasgd_merge only keep the books.
+                                  What one GPU can do when the average need not be a separate,
+                                  overlappable operation.  Needs the W x P matrix layout and d > 0;
+                                  otherwise behaves as DASGD_FUSE_STEP_MERGE */
 };
 
 /* Kernels for dasgd_profile_read. */
@@ -86,7 +92,9 @@ enum {
     DASGD_K_LOCAL_STEP_TO_SNAP = 4, /* local step storing v and the snapshot only   (20 B per element) */
     DASGD_K_STEP_MERGE         = 5, /* local step with the merge folded in          (20 + 4/W)        */
     DASGD_K_STEP_SNAP_MERGE    = 6, /* ... that also stores the snapshot             (24 + 4/W)        */
-    DASGD_K_COUNT              = 7
+    DASGD_K_STEP_MEAN          = 7, /* local step that also computes the mean        (20 + 4/W)        */
+    DASGD_K_STEP_MEAN_MERGE    = 8, /* local step with mean and merge folded in      (20 + 8/W)        */
+    DASGD_K_COUNT              = 9
 };
 
 /* Create a context for W replicas of P fp32 parameters each.
@@ -116,7 +124,8 @@ int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
 /* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
  * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots
  * (floor(d/tau)+1 slots of W x P' floats) and the averages (same number of slots of P' floats),
- * where P' pads every tensor to a multiple of 64 elements.  Returns 0 on invalid arguments. */
+ * where P' pads every tensor to a multiple of 64 elements and adds 32.  Returns 0 on invalid
+ * arguments. */
 size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
 
 /* Bind the replicas' storage.
@@ -158,9 +167,11 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
  *       pointers of the previous call (the table is re-uploaded only when it changes).
  * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
- * in the order given, replica rows back to back, base 16-byte aligned, P a multiple of 4 -- the
- * kernels address them by arithmetic alone (fastest); any other layout goes through a chunk
- * table.  Results are identical.
+ * in the order given, one common row stride ld with P <= ld < P + 32 floats and ld a multiple of 4,
+ * base 16-byte aligned -- the kernels address them by arithmetic alone (fastest; fastest of all when
+ * ld is a multiple of 32, so that rows are 128-byte aligned to each other).  The up to 31 floats
+ * between two rows are then padding that BELONGS TO THE MATRIX: the library reads and overwrites
+ * them.  Any other layout goes through a chunk table.  Results are identical.
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
 int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
 
@@ -208,8 +219,9 @@ int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begi
 
 /* Layout of the library-owned buffers inside the workspace, for inspection by tests and tools:
  * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
- * *P_padded = elements per row: P when x and v were bound as W x P matrices (rows mirror that
- * layout), otherwise every tensor padded to a multiple of 64 elements.  ESTATE if not bound. */
+ * *P_padded = elements per row: the row stride ld when x and v were bound as W x P matrices (rows
+ * mirror that layout), otherwise every tensor padded to a multiple of 64 elements (plus 32).
+ * ESTATE if not bound. */
 int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
 
 /* Locate pending average number `which` (0 = oldest): its launch step and the byte offset of its

@@ -17,10 +17,12 @@ from . import build as _build
 DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
 SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY, SCHED_OVERLAP_FREE = 0, 1, 2, 3
 K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, K_LOCAL_STEP_TO_SNAP, K_STEP_MERGE, K_STEP_SNAP_MERGE = 0, 1, 2, 3, 4, 5, 6
-FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE = 0, 1, 2
+K_STEP_MEAN, K_STEP_MEAN_MERGE = 7, 8
+FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE, FUSE_ALL = 0, 1, 2, 3
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
                 K_MEAN: "mean", K_MERGE: "merge", K_LOCAL_STEP_TO_SNAP: "local_step_to_snapshot",
-                K_STEP_MERGE: "step_merge", K_STEP_SNAP_MERGE: "step_snapshot_merge"}
+                K_STEP_MERGE: "step_merge", K_STEP_SNAP_MERGE: "step_snapshot_merge",
+                K_STEP_MEAN: "step_mean", K_STEP_MEAN_MERGE: "step_mean_merge"}
 _ERR = {DASGD_EINVAL: "DASGD_EINVAL (bad argument)", DASGD_ESTATE: "DASGD_ESTATE (call illegal in this state)",
         DASGD_ENOMEM: "DASGD_ENOMEM (workspace too small)", DASGD_EHIP: "DASGD_EHIP (HIP call failed)"}
 

@@ -36,7 +36,7 @@ struct Layout {                     // byte offsets into the workspace
     size_t chunks, xp, vp, gp[kGTables], S, A, total;
     int64_t P_pad, n_chunks;        // P_pad: elements per snapshot row / average
     std::vector<int64_t> foff;      // start of each tensor inside such a row
-    bool flat = false;              // rows are unpadded (foff = plain prefix sums, P_pad = P)
+    bool flat = false;              // rows mirror the caller's matrix (foff = plain prefix sums, P_pad = row stride)
 };
 
 }  // namespace
@@ -70,9 +70,11 @@ struct dasgd_ctx {
     bool y_in_snap = false;         // ... and ONLY the snapshot: x is stale until this step's merge
     bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
     bool merged_in_step = false;    // the latest local step already applied this step's merge
+    bool mean_in_step = false;      // ... and already computed the average that average_begin will register
     int snap_slot = 0;
     // matrix layout: x, v (and g) are W x P row-major matrices, rows back to back, 16-byte aligned
     bool xv_matrix = false, g_matrix = false;
+    int64_t ld = 0;                 // row stride of that matrix in elements (P <= ld < P + 32)
     float *x0 = nullptr, *v0 = nullptr;
     const float *g0 = nullptr;
     bool idx32 = false;             // 64 <= P/4 and W*P/4 + 64 < 2^31: the column-aware flat kernels apply
@@ -115,7 +117,9 @@ bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 // matrices, mirror that unpadded layout (so one flat index addresses x, v, g and the snapshot alike).
 // The byte offsets of the padded layout are used in both cases: the workspace size must not depend
 // on pointers that dasgd_workspace_bytes never sees.
-Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false)
+constexpr int64_t kMaxRowPad = 32;  // a matrix row may be followed by fewer than this many padding floats
+
+Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false, int64_t ld = 0)
 {
     Layout L;
     L.foff.resize(n_tensors);
@@ -127,6 +131,7 @@ Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool
         nch += (numel[t] + kChunk - 1) / kChunk;
     }
     L.flat = flat;
+    f += kMaxRowPad;                // room for the row padding of the matrix layout
     L.P_pad = f;                    // sizes below always use the padded row length
     L.n_chunks = nch;
     const size_t tbl = sizeof(void *) * (size_t)c->W * (size_t)n_tensors;
@@ -138,23 +143,32 @@ Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool
     L.S = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)c->W * (size_t)L.P_pad);
     L.A = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)L.P_pad);
     L.total = o;
-    if (flat) L.P_pad = fp;
+    if (flat) L.P_pad = ld;
     return L;
 }
 
-// True when ptr[j*n + t] == ptr[0] + j*P + (unpadded offset of t) for all j, t, base 16-byte aligned
-// and P a multiple of 4: a W x P row-major matrix with rows back to back.
+// True when ptr[j*n + t] == ptr[0] + j*ld + (unpadded offset of t) for all j, t with one row stride ld,
+// P <= ld < P + kMaxRowPad, ld a multiple of 4, base 16-byte aligned: a W x P row-major matrix whose
+// rows are back to back or separated by a little alignment padding (which then belongs to the matrix).
 template <typename T>
-bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr)
+bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr, int64_t *ld_out)
 {
-    if (c->P % 4 != 0 || (reinterpret_cast<uintptr_t>(ptr[0]) & 15u)) return false;
+    if (reinterpret_cast<uintptr_t>(ptr[0]) & 15u) return false;
+    int64_t ld = c->P;
+    if (c->W > 1) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(ptr[0]), b = reinterpret_cast<uintptr_t>(ptr[n_tensors]);
+        if (b <= a || (b - a) % sizeof(float)) return false;
+        ld = (int64_t)((b - a) / sizeof(float));
+    }                               // (one row: nothing tells a stride, so ld = P)
+    if (ld < c->P || ld - c->P >= kMaxRowPad || ld % 4 != 0) return false;
     for (int j = 0; j < c->W; ++j) {
         int64_t off = 0;
         for (int t = 0; t < n_tensors; ++t) {
-            if (ptr[(size_t)j * n_tensors + t] != ptr[0] + (int64_t)j * c->P + off) return false;
+            if (ptr[(size_t)j * n_tensors + t] != ptr[0] + (int64_t)j * ld + off) return false;
             off += numel[t];
         }
     }
+    *ld_out = ld;
     return true;
 }
 
@@ -270,7 +284,7 @@ int dasgd_set_schedule(dasgd_ctx *c, int schedule)
 
 int dasgd_set_fusion(dasgd_ctx *c, int fusion)
 {
-    if (!c || fusion < DASGD_FUSE_NONE || fusion > DASGD_FUSE_STEP_MERGE) return DASGD_EINVAL;
+    if (!c || fusion < DASGD_FUSE_NONE || fusion > DASGD_FUSE_ALL) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->fusion = fusion;
     return DASGD_OK;
@@ -314,8 +328,9 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         if (!x[r] || !v[r]) return DASGD_EINVAL;
         if ((reinterpret_cast<uintptr_t>(x[r]) | reinterpret_cast<uintptr_t>(v[r])) & 3u) return DASGD_EINVAL;
     }
-    const bool matrix = is_matrix(c, n_tensors, numel, x) && is_matrix(c, n_tensors, numel, v);
-    Layout L = make_layout(c, n_tensors, numel, matrix);
+    int64_t ldx = 0, ldv = 0;
+    const bool matrix = is_matrix(c, n_tensors, numel, x, &ldx) && is_matrix(c, n_tensors, numel, v, &ldv) && ldx == ldv;
+    Layout L = make_layout(c, n_tensors, numel, matrix, ldx);
     if (workspace_bytes < L.total) return DASGD_ENOMEM;
 
     // chunk table
@@ -335,9 +350,10 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     c->numel.assign(numel, numel + n_tensors);
     c->lay = L;
     c->xv_matrix = matrix;
+    c->ld = matrix ? ldx : 0;
     c->x0 = x[0];
     c->v0 = v[0];
-    c->idx32 = matrix && c->P / 4 >= 64 && (int64_t)c->W * c->P / 4 + 64 < (1ll << 31) && (int64_t)decode_grid((unsigned)c->W, (unsigned)(c->P / 4)) < (1ll << 31);
+    c->idx32 = matrix && c->ld / 4 >= 64 && (int64_t)c->W * c->ld / 4 + 64 < (1ll << 31) && (int64_t)decode_grid((unsigned)c->W, (unsigned)(c->ld / 4)) < (1ll << 31);
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
@@ -403,9 +419,11 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                                            : (!c->pending.empty() && c->pending.front().launch_step == k - c->d);
     const bool snap = snap_step && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
     // fold the merge into this kernel?  (not for d == 0: that merge needs the mean of this step's own output)
-    const bool fold = merge_follows && c->d > 0 && c->fusion == DASGD_FUSE_STEP_MERGE;
+    const bool fold = merge_follows && c->d > 0 && c->fusion >= DASGD_FUSE_STEP_MERGE;
     int mode = kStoreX;
     if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
+    // everything in one kernel?  (decided below once the gradient layout is known)
+    bool all = false;
     const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
 
     if (!c->dry) {
@@ -430,7 +448,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 HIPCHK(c, hipMemcpyAsync(c->ws + c->lay.gp[b], stage, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
                 c->g_cached.assign(g, g + rows);
                 c->g_cur = b;
-                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g);
+                int64_t ldg = 0;
+                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g, &ldg) && ldg == c->ld;
                 c->g0 = g[0];
             }
         }
@@ -452,21 +471,47 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             }
         }
         if (fold) A = avg_ptr(c, c->pending.front().slot);
-        const int kid = fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
+        all = c->fusion == DASGD_FUSE_ALL && c->d > 0 && c->xv_matrix && c->g_matrix &&
+              c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY && snap;
+        const int kid = all ? (fold ? DASGD_K_STEP_MEAN_MERGE : DASGD_K_STEP_MEAN)
+                      : fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
         int rec;
         int rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         const bool flat = c->xv_matrix && c->g_matrix && (!fold || c->idx32);
-        if (flat) {
-            const int64_t n4 = (int64_t)c->W * c->P / 4;
+        if (all) {
+            const int64_t row4 = c->ld / 4;
+            const dim3 agrid((unsigned)((row4 + kWave - 1) / kWave));
+            v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0);
+            const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
+            const v4f *Ao = reinterpret_cast<const v4f *>(A);
+            v4f *An = snap ? reinterpret_cast<v4f *>(avg_ptr(c, slot)) : nullptr;
+            const float inv_w = 1.0f / (float)c->W;
+#define DASGD_LAUNCH_ALL(WT, MEAN, MERGE)                                                                       \
+    hipLaunchKernelGGL((k_step_all_flat<WT, MEAN, MERGE>), agrid, dim3(kWave), 0, c->main_s, x4, v4, g4, Ao, An, \
+                       row4, c->W, c->lr, c->momentum, c->wd, om, inv_w)
+#define DASGD_LAUNCH_ALL_W(MEAN, MERGE)                                                                         \
+    switch (c->W) {                                                                                             \
+    case 1:  DASGD_LAUNCH_ALL(1, MEAN, MERGE);  break;                                                          \
+    case 2:  DASGD_LAUNCH_ALL(2, MEAN, MERGE);  break;                                                          \
+    case 4:  DASGD_LAUNCH_ALL(4, MEAN, MERGE);  break;                                                          \
+    case 8:  DASGD_LAUNCH_ALL(8, MEAN, MERGE);  break;                                                          \
+    case 16: DASGD_LAUNCH_ALL(16, MEAN, MERGE); break;                                                          \
+    default: DASGD_LAUNCH_ALL(0, MEAN, MERGE);  break;                                                          \
+    }
+            if (fold) { DASGD_LAUNCH_ALL_W(true, true) } else { DASGD_LAUNCH_ALL_W(true, false) }
+#undef DASGD_LAUNCH_ALL_W
+#undef DASGD_LAUNCH_ALL
+        } else if (flat) {
+            const int64_t n4 = (int64_t)c->W * c->ld / 4;
             const dim3 grid((unsigned)((n4 + kWave - 1) / kWave));
             v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0), *s4 = reinterpret_cast<v4f *>(S);
             const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
             if (fold) {
                 const v4f *A4 = reinterpret_cast<const v4f *>(A);
-                const unsigned row4 = (unsigned)(c->P / 4);
+                const unsigned row4 = (unsigned)(c->ld / 4);
                 const dim3 fgrid(decode_grid((unsigned)c->W, row4));
 #define DASGD_LAUNCH_FOLD(SNAP, WT)                                                                             \
     hipLaunchKernelGGL((k_step_merge_flat<SNAP, WT>), fgrid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4,     \
@@ -514,6 +559,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     c->snap_valid = snap_step;
     c->y_in_snap = (mode == kStoreS);
     c->merged_in_step = fold;
+    c->mean_in_step = all;
     c->mean_deferred = false;
     c->snap_slot = (int)(c->n_launched % c->slots);
     return DASGD_OK;
@@ -525,7 +571,7 @@ int dasgd_average_begin(dasgd_ctx *c)
     if (!c->bound || !begin_due(c) || !c->snap_valid) return DASGD_ESTATE;
     if ((int)c->pending.size() >= c->slots) return DASGD_ESTATE;
     const int slot = c->snap_slot;
-    if (!c->dry && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY) {
+    if (!c->dry && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY && !c->mean_in_step) {
         // The mean has d local steps of slack, the merge of this step has none: when a merge of an
         // OLDER average is still to come in this step, the mean is launched right behind it, so the
         // two bandwidth-bound kernels do not run against each other and the mean overlaps what the
@@ -537,7 +583,8 @@ int dasgd_average_begin(dasgd_ctx *c)
             if (rc != DASGD_OK) return rc;
         }
     }
-    c->pending.push_back(Pending{c->n_done - 1, slot, false});
+    c->pending.push_back(Pending{c->n_done - 1, slot, c->mean_in_step});   // computed on the main stream: nothing to wait for
+    c->mean_in_step = false;
     c->n_launched += 1;
     c->begun_for_k = true;
     return DASGD_OK;
@@ -556,7 +603,7 @@ int dasgd_merge(dasgd_ctx *c)
         int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         if (c->xv_matrix && c->idx32) {
-            const int64_t row4 = c->P / 4;
+            const int64_t row4 = c->ld / 4;
             v4f *X4 = reinterpret_cast<v4f *>(c->x0);
             const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
             const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));

@@ -300,6 +300,79 @@ k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4,
     }
 }
 
+// Matrix layout, everything of one iteration in ONE pass: a wavefront owns a window of 64 columns of
+// ALL W rows; per lane it updates the W replicas of its column (local step), sums their new values
+// into the average that is launched at this step (MEAN) and folds the average launched d steps ago
+// into them (MERGE).  No snapshot and no separate mean kernel: 20 + 8/W bytes per replica-element
+// for a step that does all three.  The price is row-strided access: unless P is a multiple of 32 the
+// rows are not 128-byte aligned to each other and the kilobytes a wave touches straddle cache lines.
+// Same operations in the same order as k_local_step_flat + k_mean + k_merge_flat (identical bits).
+template <int WT, bool MEAN, bool MERGE>   // WT > 0: W known at compile time (tree sum); 0: any W
+__global__ void __launch_bounds__(kWave)
+k_step_all_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g,
+                const v4f *__restrict__ A_old, v4f *__restrict__ A_new, int64_t row4, int W,
+                float lr, float momentum, float wd, float om, float inv_w)
+{
+    const int64_t c = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (c >= row4) return;
+    v4f a = {0.f, 0.f, 0.f, 0.f};
+    if (MERGE) a = ld4<false>(A_old + c);
+    if constexpr (WT > 0) {
+        v4f y[WT];
+        constexpr int JB = WT < 4 ? WT : 4;
+#pragma unroll
+        for (int j0 = 0; j0 < WT; j0 += JB) {
+            v4f vr[JB], gr[JB];
+#pragma unroll
+            for (int j = 0; j < JB; ++j) {
+                const int64_t i = (int64_t)(j0 + j) * row4 + c;
+                y[j0 + j] = ld4<true>(x + i);
+                vr[j] = ld4<true>(v + i);
+                gr[j] = ld4<true>(g + i);
+            }
+#pragma unroll
+            for (int j = 0; j < JB; ++j) {
+                const int64_t i = (int64_t)(j0 + j) * row4 + c;
+                sgd4(y[j0 + j], vr[j], gr[j], lr, momentum, wd);
+                st4<true>(v + i, vr[j]);
+                st4<true>(x + i, MERGE ? merge4(y[j0 + j], a, om) : y[j0 + j]);
+            }
+        }
+        if (MEAN) st4<false>(A_new + c, tree_sum<0, WT>(y) * inv_w);
+    } else {
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        int j = 0;
+        for (; j + 4 <= W; j += 4) {
+            v4f y[4], vr[4], gr[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = (int64_t)(j + u) * row4 + c;
+                y[u] = ld4<true>(x + i);
+                vr[u] = ld4<true>(v + i);
+                gr[u] = ld4<true>(g + i);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = (int64_t)(j + u) * row4 + c;
+                sgd4(y[u], vr[u], gr[u], lr, momentum, wd);
+                st4<true>(v + i, vr[u]);
+                st4<true>(x + i, MERGE ? merge4(y[u], a, om) : y[u]);
+            }
+            acc += (y[0] + y[1]) + (y[2] + y[3]);
+        }
+        for (; j < W; ++j) {
+            const int64_t i = (int64_t)j * row4 + c;
+            v4f y = ld4<true>(x + i), vr = ld4<true>(v + i);
+            const v4f gr = ld4<true>(g + i);
+            sgd4(y, vr, gr, lr, momentum, wd);
+            st4<true>(v + i, vr);
+            st4<true>(x + i, MERGE ? merge4(y, a, om) : y);
+            acc += y;
+        }
+        if (MEAN) st4<false>(A_new + c, acc * inv_w);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Delayed merge: x_j <- y_j + (1 - xi)(A - y_j) for every replica j, where y_j is the value after the
 // local step (held in x_j, or in the snapshot when the local step stored only that).

@@ -22,8 +22,10 @@ TOL = 1e-5      # bound on |x_gpu - x_oracle| / parameter scale, per tensor, who
 class GpuRun:
     """Device state of one configuration bound to a library context.
 
-    layout "arena": one flat allocation per replica for each of x, v, g; tensors are views at
-    the unpadded offsets (so odd-sized tensors make their successors 16-byte misaligned).
+    layout "arena": x, v, g each one W x P allocation, rows back to back; tensors are views at the
+    unpadded offsets (so odd-sized tensors make their successors 16-byte misaligned).
+    layout "arena_padded": the same with the row stride rounded up to a multiple of 32 floats
+    (plus 32 when it already is one, so that there is always padding), padding poisoned with NaN.
     layout "separate": every tensor is its own allocation.
     """
 
@@ -40,10 +42,13 @@ class GpuRun:
         n = cfg.params.n_tensors
         with torch.cuda.stream(self.main):
             w0 = wl.init_weights(cfg, self.dev)
-            if layout == "arena":
-                self.x_flat = w0.unsqueeze(0).repeat(W, 1).contiguous()
-                self.v_flat = torch.zeros(W, P, device=self.dev)
-                self.g_flat = torch.zeros(W, P, device=self.dev)
+            if layout in ("arena", "arena_padded"):
+                ld = P if layout == "arena" else (P + 31) // 32 * 32 + (28 if P % 32 == 0 else 0)
+                full = [torch.full((W, ld), float("nan"), device=self.dev) for _ in range(3)]
+                self.x_flat, self.v_flat, self.g_flat = (a[:, :P] for a in full)
+                self.x_flat.copy_(w0.unsqueeze(0).expand(W, P))
+                self.v_flat.zero_()
+                self.g_flat.zero_()
                 view = lambda a: [[a[j, off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
                 self.x, self.v, self.g = view(self.x_flat), view(self.v_flat), view(self.g_flat)
             elif layout == "separate":

@@ -49,6 +49,10 @@ def test_local_step_kernel(layout, pset):
     cfg = small(tau=1000, d=0, W=3, steps=3, params=custom_param_set(SETS[pset]))
     run = GpuRun(cfg, layout=layout)
     assert (run.opt.layout()[1] == cfg.P) == (pset == "matrix")      # which addressing is in use
+    if pset == "table":      # the same set in padded rows (stride 26816) does qualify as a matrix
+        pad = GpuRun(cfg, layout="arena_padded")
+        assert pad.opt.layout()[1] == (cfg.P + 31) // 32 * 32
+        pad.close()
     x = run.weights().astype(np.float64); v = np.zeros_like(x)
     for k in range(3):
         run.step()
@@ -96,22 +100,27 @@ def test_merge_kernel(layout, xi, pset):
 # ------------------------------------------------------------------------------------------------
 # whole runs, small
 @pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 1, 4), (1, 2, 8), (4, 2, 16), (1, 4, 4), (3, 3, 5), (2, 5, 3), (5, 4, 2), (1, 2, 1)])
-@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table")])
+@pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table"),
+                                         ("arena_padded", "table"), ("arena_padded", "matrix_even")])
 def test_small_runs_match_oracle(tau, d, W, layout, pset):
     cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
     both_oracles(cfg, run_gpu(cfg, layout=layout))
 
 
-@pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 2, 8), (4, 2, 16), (2, 4, 3), (3, 3, 5)])
+@pytest.mark.parametrize("tau,d,W", [(1, 0, 4), (1, 2, 8), (4, 2, 16), (2, 4, 3), (3, 3, 5), (1, 1, 2), (2, 2, 1)])
 @pytest.mark.parametrize("layout,pset", [("arena", "table"), ("arena", "matrix"), ("separate", "table"),
-                                         ("arena", "matrix_tiny"), ("arena", "matrix_even")])
+                                         ("arena", "matrix_tiny"), ("arena", "matrix_even"),
+                                         ("arena_padded", "table"), ("arena_padded", "matrix"), ("arena_padded", "matrix_even")])
 def test_fusion_levels_agree_bit_for_bit(tau, d, W, layout, pset):
-    """Separate kernels, merge-from-snapshot and merge-folded-into-the-local-step do the same
-    operations on the same values in the same order: identical bits; and they match the oracle."""
+    """Separate kernels, merge-from-snapshot, merge-folded-into-the-local-step and everything-in-one-
+    kernel do the same operations on the same values in the same order: identical bits; and they
+    match the oracle."""
     import paper_2006_00441_amd as pkg
     cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
-    runs = [run_gpu(cfg, layout=layout, fusion=f) for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE)]
-    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+    runs = [run_gpu(cfg, layout=layout, fusion=f)
+            for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL)]
+    for r in runs[1:]:
+        assert np.array_equal(runs[0], r)
     both_oracles(cfg, runs[0])
 
 
@@ -126,7 +135,7 @@ def test_every_step_matches_oracle_quadratic_small():
     assert max(errs) <= TOL
 
 
-@pytest.mark.parametrize("fusion", [0, 1, 2])
+@pytest.mark.parametrize("fusion", [0, 1, 2, 3])
 @pytest.mark.parametrize("pset", ["table", "matrix"])
 def test_schedules_give_identical_results(pset, fusion):
     """Side-stream and single-stream schedules run the same kernels on the same data: bit-equal."""
@@ -196,8 +205,9 @@ def test_config_quadratic_full_every_step():
     both_oracles(cfg, run_gpu(cfg))
 
 
-@pytest.mark.parametrize("name,fusion", [("resnet50_w8", 2), ("resnet50_w8", 1), ("resnet50_w8", 0),
-                                         ("resnet50_w16", 2), ("bert_large_w4", 2), ("bert_large_w4", 1)])
+@pytest.mark.parametrize("name,fusion", [("resnet50_w8", 2), ("resnet50_w8", 1), ("resnet50_w8", 0), ("resnet50_w8", 3),
+                                         ("resnet50_w16", 2), ("resnet50_w16", 3), ("bert_large_w4", 2),
+                                         ("bert_large_w4", 1), ("bert_large_w4", 3)])
 def test_config_full_size_sampled(name, fusion):
     """Full-size run in the launch configuration the benchmark times; compared on sampled
     coordinates (all small tensors entirely, chunk boundaries, heads, tails, random elements):
