@@ -146,6 +146,31 @@ def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
     return wall, ev_ms, kernels
 
 
+def fusion_all_region(cfg, steps: int, warmup: int):
+    """The same workload with the mean folded into the local-step kernel as well (fusion level 3: one
+    kernel per step, nothing on the side stream).  Reported beside the headline, never as it."""
+    import paper_2006_00441_amd as pkg
+    keep = Bench.fusion
+    Bench.fusion = pkg.FUSE_ALL
+    try:
+        b = Bench(cfg, pkg.SCHED_OVERLAP)
+        for _ in range(warmup):
+            b.step()
+        b.opt.profile(PROFILE_EVERY, 4 * steps + 16)
+        wall, _ = b.run(steps, 0)
+        ks = {}
+        for kid, name in pkg.KERNEL_NAMES.items():
+            ms, n, launched = b.opt.profile_read(kid)
+            if n:
+                bts = algorithmic_bytes_per_rp(name, cfg.W) * cfg.W * cfg.P
+                ks[name] = {"avg_ms": round(ms / n, 5), "launches": launched,
+                            "frac_of_hbm_peak": round(bts / (ms / n * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        b.close()
+    finally:
+        Bench.fusion = keep
+    return {"ms_per_step": wall / steps * 1e3, "value": cfg.W * cfg.P * steps / wall, "kernels": ks}
+
+
 def overlap_study(cfg, steps: int, warmup: int, gemm: bool):
     """Three schedules with identical kernels: S0 everything on one stream, S1 the mean on the side
     stream, F = S0 without snapshot and mean (timing floor).  hidden = (T(S0)-T(S1)) / (T(S0)-T(F))."""
@@ -336,6 +361,8 @@ def main() -> int:
                           "with_compute_stand_in": overlap_study(cfg, k, 10, gemm=True)}
         if cfg.kind == "external" and cfg.P % 4 == 0 and args.layout == "matrix":
             out["algorithms"] = compare_algorithms(cfg, 40, 8)
+    if not args.only_timed and args.layout == "matrix" and args.fusion is None:
+        out["fusion_all"] = fusion_all_region(cfg, args.steps, args.warmup)
     if not args.only_timed and not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

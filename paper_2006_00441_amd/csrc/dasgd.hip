@@ -229,14 +229,21 @@ int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A, int64_t r
     v4f *A4 = reinterpret_cast<v4f *>(A);
     const float inv_w = 1.0f / (float)c->W;
     auto grid = [&](int U) { return dim3((unsigned)(((n4 + (int64_t)kWave * U - 1) / ((int64_t)kWave * U) + 63) / 64 * 64)); };
+    const bool runs = (row_elems % 32) != 0;         // rows not 128-byte aligned to each other
+#define DASGD_LAUNCH_MEAN(WT)                                                                                   \
+    do {                                                                                                        \
+        if (runs) hipLaunchKernelGGL((k_mean<WT, 1, true, true>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
+        else      hipLaunchKernelGGL((k_mean<WT, 1, true, false>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
+    } while (0)
     switch (c->W) {
-    case 1:  hipLaunchKernelGGL((k_mean<1, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 2:  hipLaunchKernelGGL((k_mean<2, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 4:  hipLaunchKernelGGL((k_mean<4, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 8:  hipLaunchKernelGGL((k_mean<8, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    case 16: hipLaunchKernelGGL((k_mean<16, 1, true>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
-    default: hipLaunchKernelGGL((k_mean<0, 1, true>),  grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); break;
+    case 1:  DASGD_LAUNCH_MEAN(1);  break;
+    case 2:  DASGD_LAUNCH_MEAN(2);  break;
+    case 4:  DASGD_LAUNCH_MEAN(4);  break;
+    case 8:  DASGD_LAUNCH_MEAN(8);  break;
+    case 16: DASGD_LAUNCH_MEAN(16); break;
+    default: DASGD_LAUNCH_MEAN(0);  break;
     }
+#undef DASGD_LAUNCH_MEAN
     HIPCHK(c, hipGetLastError());
     return DASGD_OK;
 }

@@ -253,17 +253,19 @@ template <int LO, int HI> __device__ __forceinline__ v4f tree_sum(const v4f *r) 
 // 128-bit column and reads it from all W rows (W independent loads in flight), so the reduction
 // needs no cross-lane traffic.  (4 + 4/W) bytes per replica-element.  Single-wave workgroups.  WT > 0: W known at compile
 // time, the whole column set is loaded before the tree sum; WT == 0: any W, four rows at a time.
-template <int WT, int U, bool NT>
+template <int WT, int U, bool NT, bool RUNS>
 __global__ void __launch_bounds__(kWave)
 k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4, int W, float inv_w)
 {
     // The mean runs beside whatever the caller has on the main stream (typically dense compute that
     // leaves wave slots free but keeps the issue ports busy): its few instructions go first.
     __builtin_amdgcn_s_setprio(3);
-    // Eight consecutive 64-column windows go to the same XCD back to back: when the rows are not
-    // 128-byte aligned relative to each other, the cache line two neighbouring windows share is
-    // then found in that XCD's L2 instead of being fetched from HBM twice.
-    const int64_t blk = ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7);
+    // RUNS: eight consecutive 64-column windows go to the same XCD back to back.  When the rows are
+    // not 128-byte aligned relative to each other, the cache line two neighbouring windows share is
+    // then found in that XCD's L2 instead of being fetched from HBM twice.  Aligned rows share no
+    // lines and keep the plain order, which is a little faster.
+    const int64_t blk = RUNS ? ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7)
+                             : (int64_t)blockIdx.x;
     const int64_t base = blk * (kWave * U) + threadIdx.x;
     if constexpr (WT > 0) {
         v4f r[U][WT];
