@@ -235,14 +235,20 @@ int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A, int64_t r
         if (runs) hipLaunchKernelGGL((k_mean<WT, 1, true, true>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
         else      hipLaunchKernelGGL((k_mean<WT, 1, true, false>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
     } while (0)
-    switch (c->W) {
+#define DASGD_LAUNCH_MEAN_LDS(WT, NW)                                                                           \
+    do {                                                                                                        \
+        if (runs) hipLaunchKernelGGL((k_mean_lds<WT, NW, true>), grid(1), dim3(kWave * NW), 0, s, S4, A4, n4, n4, inv_w); \
+        else      hipLaunchKernelGGL((k_mean_lds<WT, NW, false>), grid(1), dim3(kWave * NW), 0, s, S4, A4, n4, n4, inv_w); \
+    } while (0)
+    switch (c->W) {             // rows split over wavefronts + LDS where that measured faster
     case 1:  DASGD_LAUNCH_MEAN(1);  break;
     case 2:  DASGD_LAUNCH_MEAN(2);  break;
-    case 4:  DASGD_LAUNCH_MEAN(4);  break;
-    case 8:  DASGD_LAUNCH_MEAN(8);  break;
-    case 16: DASGD_LAUNCH_MEAN(16); break;
+    case 4:  DASGD_LAUNCH_MEAN_LDS(4, 4);  break;
+    case 8:  DASGD_LAUNCH_MEAN_LDS(8, 4);  break;
+    case 16: DASGD_LAUNCH_MEAN_LDS(16, 8); break;
     default: DASGD_LAUNCH_MEAN(0);  break;
     }
+#undef DASGD_LAUNCH_MEAN_LDS
 #undef DASGD_LAUNCH_MEAN
     HIPCHK(c, hipGetLastError());
     return DASGD_OK;
