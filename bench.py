@@ -265,8 +265,17 @@ def cpu_baseline(cfg, budget_s: float = 12.0):
     for _ in range(n):
         o.step(g)
     dt = time.perf_counter() - t0
+    # the same oracle on one thread, a few steps (context: what one host core does)
+    oracle.set_threads(1)
+    n1 = max(cfg.tau, min(n, int(2.0 / max(one * threads / 4, 1e-6))) // cfg.tau * cfg.tau)
+    t0 = time.perf_counter()
+    for _ in range(n1):
+        o.step(g)
+    dt1 = time.perf_counter() - t0
+    oracle.set_threads(threads)
     o.close()
     return {"value": cfg.W * cfg.P * n / dt, "unit": "replica-params/s", "cores": threads, "kind": "oracle",
+            "single_thread_value": cfg.W * cfg.P * n1 / dt1, "single_thread_steps": n1,
             "sample": f"{n} steps of {cfg.name} at full size (W={cfg.W}, P={cfg.P}), fp32 oracle, "
                       f"{threads} OpenMP threads, {dt:.1f} s", "ms_per_step": dt / n * 1e3}
 

@@ -72,7 +72,7 @@ struct dasgd_ctx {
     bool merged_in_step = false;    // the latest local step already applied this step's merge
     bool mean_in_step = false;      // ... and already computed the average that average_begin will register
     int snap_slot = 0;
-    // matrix layout: x, v (and g) are W x P row-major matrices, rows back to back, 16-byte aligned
+    // matrix layout: x, v (and g) are W x P row-major matrices with one row stride, 16-byte aligned
     bool xv_matrix = false, g_matrix = false;
     int64_t ld = 0;                 // row stride of that matrix in elements (P <= ld < P + 32)
     float *x0 = nullptr, *v0 = nullptr;
@@ -113,10 +113,10 @@ bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 }
 
 // Rows of the library-owned buffers either pad every tensor to a 256-byte boundary (so the table
-// kernels can always use 128-bit accesses on them) or, when the caller's x and v are plain W x P
-// matrices, mirror that unpadded layout (so one flat index addresses x, v, g and the snapshot alike).
-// The byte offsets of the padded layout are used in both cases: the workspace size must not depend
-// on pointers that dasgd_workspace_bytes never sees.
+// kernels can always use 128-bit accesses on them) or, when the caller's x and v are W x P matrices,
+// mirror that layout, row stride included (so one flat index addresses x, v, g and the snapshot
+// alike).  The byte offsets of the padded layout are used in both cases: the workspace size must not
+// depend on pointers that dasgd_workspace_bytes never sees.
 constexpr int64_t kMaxRowPad = 32;  // a matrix row may be followed by fewer than this many padding floats
 
 Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false, int64_t ld = 0)
