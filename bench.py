@@ -35,7 +35,8 @@ def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
             "step_snapshot_merge": 24.0 + 4.0 / W,  # ... + write the snapshot
             "step_mean": 20.0 + 4.0 / W,           # local step that also writes the mean
             "step_mean_merge": 20.0 + 8.0 / W,     # local step, mean and merge in one pass
-            "mean": 4.0 + 4.0 / W,                 # read W snapshot rows, write one average
+            "mean": 4.0 + 4.0 / W,                 # read W rows, write one average
+            "mean_reconstruct": 4.0 + 8.0 / W,     # ... and read the merged-in average to undo the merge
             "merge": 8.0 + 4.0 / W}[kernel]        # read x and the average (once), write x
 
 

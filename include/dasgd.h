@@ -83,6 +83,20 @@ enum {
                                   otherwise behaves as DASGD_FUSE_STEP_MERGE */
 };
 
+/* Where the average finds the weights it averages (dasgd_set_snapshot). */
+enum {
+    DASGD_SNAPSHOT_COPY      = 0, /* the local-step kernel stores them into a snapshot buffer (an extra
+                                     4 bytes per element); the mean may then take its full d steps */
+    DASGD_SNAPSHOT_ZERO_COPY = 1  /* default: the live weights are the snapshot.  The mean reads x itself
+                                     and the next kernel that writes x waits for it.  On a step that also
+                                     merges an older average A (folded into the local step, so that x
+                                     already holds x' = xi y + (1 - xi) A), the mean of the y is recovered
+                                     as (mean x' - (1 - xi) A) / xi in double precision: same quantity,
+                                     rounding differs in the last bits.  Used when: matrix layout;
+                                     schedule OVERLAP or SERIAL; fusion level 2; and either no merge falls
+                                     on the step or xi >= 1/8.  Otherwise the copy is made. */
+};
+
 /* Kernels for dasgd_profile_read. */
 enum {
     DASGD_K_LOCAL_STEP         = 0, /* local step storing x, v                      (20 B per element) */
@@ -94,7 +108,8 @@ enum {
     DASGD_K_STEP_SNAP_MERGE    = 6, /* ... that also stores the snapshot             (24 + 4/W)        */
     DASGD_K_STEP_MEAN          = 7, /* local step that also computes the mean        (20 + 4/W)        */
     DASGD_K_STEP_MEAN_MERGE    = 8, /* local step with mean and merge folded in      (20 + 8/W)        */
-    DASGD_K_COUNT              = 9
+    DASGD_K_MEAN_RECONSTRUCT   = 9, /* W-way mean of the live weights, merge undone  (4 + 8/W)         */
+    DASGD_K_COUNT              = 10
 };
 
 /* Create a context for W replicas of P fp32 parameters each.
@@ -120,6 +135,9 @@ int dasgd_set_schedule(dasgd_ctx *ctx, int schedule);
 
 /* Choose the fusion level (DASGD_FUSE_*).  Only legal while no average is pending. */
 int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
+
+/* Choose where the average reads the weights (DASGD_SNAPSHOT_*).  Only legal while no average is pending. */
+int dasgd_set_snapshot(dasgd_ctx *ctx, int mode);
 
 /* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
  * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots

@@ -17,12 +17,14 @@ from . import build as _build
 DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
 SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY, SCHED_OVERLAP_FREE = 0, 1, 2, 3
 K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, K_LOCAL_STEP_TO_SNAP, K_STEP_MERGE, K_STEP_SNAP_MERGE = 0, 1, 2, 3, 4, 5, 6
-K_STEP_MEAN, K_STEP_MEAN_MERGE = 7, 8
+K_STEP_MEAN, K_STEP_MEAN_MERGE, K_MEAN_RECONSTRUCT = 7, 8, 9
+SNAPSHOT_COPY, SNAPSHOT_ZERO_COPY = 0, 1
 FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE, FUSE_ALL = 0, 1, 2, 3
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
                 K_MEAN: "mean", K_MERGE: "merge", K_LOCAL_STEP_TO_SNAP: "local_step_to_snapshot",
                 K_STEP_MERGE: "step_merge", K_STEP_SNAP_MERGE: "step_snapshot_merge",
-                K_STEP_MEAN: "step_mean", K_STEP_MEAN_MERGE: "step_mean_merge"}
+                K_STEP_MEAN: "step_mean", K_STEP_MEAN_MERGE: "step_mean_merge",
+                K_MEAN_RECONSTRUCT: "mean_reconstruct"}
 _ERR = {DASGD_EINVAL: "DASGD_EINVAL (bad argument)", DASGD_ESTATE: "DASGD_ESTATE (call illegal in this state)",
         DASGD_ENOMEM: "DASGD_ENOMEM (workspace too small)", DASGD_EHIP: "DASGD_EHIP (HIP call failed)"}
 
@@ -39,6 +41,7 @@ EXPORTS = {
     "dasgd_set_lr": (ctypes.c_int, [_vp, ctypes.c_float]),
     "dasgd_set_schedule": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_set_fusion": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "dasgd_set_snapshot": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_workspace_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int, _pi64]),
     "dasgd_bind": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, _pp, _pp, _vp, ctypes.c_size_t, _vp, _vp]),
     "dasgd_bind_dry_run": (ctypes.c_int, [_vp, ctypes.c_int, _pi64]),
@@ -142,6 +145,9 @@ class DaSGD:
 
     def set_fusion(self, fusion: int) -> None:
         self._check("dasgd_set_fusion", self._lib.dasgd_set_fusion(self._h, int(fusion)))
+
+    def set_snapshot(self, mode: int) -> None:
+        self._check("dasgd_set_snapshot", self._lib.dasgd_set_snapshot(self._h, int(mode)))
 
     def workspace_bytes(self, numel: Sequence[int]) -> int:
         arr = (ctypes.c_int64 * len(numel))(*[int(n) for n in numel])

@@ -48,6 +48,7 @@ struct dasgd_ctx {
     float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
     int schedule = DASGD_SCHED_OVERLAP;
     int fusion = DASGD_FUSE_STEP_MERGE;
+    int snapshot = DASGD_SNAPSHOT_ZERO_COPY;
     int slots = 1;
     // binding
     bool bound = false, dry = false;
@@ -71,6 +72,10 @@ struct dasgd_ctx {
     bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
     bool merged_in_step = false;    // the latest local step already applied this step's merge
     bool mean_in_step = false;      // ... and already computed the average that average_begin will register
+    bool zc = false;                // the latest local step stored no snapshot: the mean reads x itself
+    bool zc_recon = false;          // ... and x already holds the merged weights: undo the merge on the mean
+    int zc_old_slot = 0;            // ... with the average in this slot
+    float zc_xi = 0.25f;            // ... and this xi
     int snap_slot = 0;
     // matrix layout: x, v (and g) are W x P row-major matrices with one row stride, 16-byte aligned
     bool xv_matrix = false, g_matrix = false;
@@ -303,6 +308,14 @@ int dasgd_set_fusion(dasgd_ctx *c, int fusion)
     return DASGD_OK;
 }
 
+int dasgd_set_snapshot(dasgd_ctx *c, int mode)
+{
+    if (!c || (mode != DASGD_SNAPSHOT_COPY && mode != DASGD_SNAPSHOT_ZERO_COPY)) return DASGD_EINVAL;
+    if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
+    c->snapshot = mode;
+    return DASGD_OK;
+}
+
 size_t dasgd_workspace_bytes(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 {
     if (!shapes_ok(c, n_tensors, numel)) return 0;
@@ -409,10 +422,23 @@ static int launch_average(dasgd_ctx *c, int slot)
         s = c->side_s;
     }
     int rec;
-    int rc = prof_open(c, DASGD_K_MEAN, s, &rec);
+    int rc = prof_open(c, c->zc && c->zc_recon ? DASGD_K_MEAN_RECONSTRUCT : DASGD_K_MEAN, s, &rec);
     if (rc != DASGD_OK) return rc;
-    rc = launch_mean(c, s, snap_ptr(c, slot), avg_ptr(c, slot), c->lay.P_pad);
-    if (rc != DASGD_OK) return rc;
+    if (c->zc && c->zc_recon) {
+        const int64_t n4 = c->ld / 4;
+        const unsigned grid = (unsigned)(((n4 + kWave - 1) / kWave + 63) / 64 * 64);
+        const v4f *X4 = reinterpret_cast<const v4f *>(c->x0), *Ao = reinterpret_cast<const v4f *>(avg_ptr(c, c->zc_old_slot));
+        v4f *An = reinterpret_cast<v4f *>(avg_ptr(c, slot));
+        const double om = (double)(1.0f - c->zc_xi), inv_xi = 1.0 / (double)c->zc_xi, inv_w = 1.0 / (double)c->W;
+        if (c->ld % 32)
+            hipLaunchKernelGGL((k_mean_reconstruct<4, true>), dim3(grid), dim3(kWave * 4), 0, s, X4, Ao, An, n4, n4, c->W, inv_w, om, inv_xi);
+        else
+            hipLaunchKernelGGL((k_mean_reconstruct<4, false>), dim3(grid), dim3(kWave * 4), 0, s, X4, Ao, An, n4, n4, c->W, inv_w, om, inv_xi);
+        HIPCHK(c, hipGetLastError());
+    } else {
+        rc = launch_mean(c, s, c->zc ? c->x0 : snap_ptr(c, slot), avg_ptr(c, slot), c->lay.P_pad);
+        if (rc != DASGD_OK) return rc;
+    }
     rc = prof_close(c, s, rec);
     if (rc != DASGD_OK) return rc;
     if (side_stream_mean(c)) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
@@ -435,6 +461,11 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     const bool fold = merge_follows && c->d > 0 && c->fusion >= DASGD_FUSE_STEP_MERGE;
     int mode = kStoreX;
     if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
+    // zero-copy snapshot: store none, let the mean read x (see DASGD_SNAPSHOT_ZERO_COPY)
+    const bool zc = snap && c->snapshot == DASGD_SNAPSHOT_ZERO_COPY && c->xv_matrix && c->fusion == DASGD_FUSE_STEP_MERGE &&
+                    (c->schedule == DASGD_SCHED_OVERLAP || c->schedule == DASGD_SCHED_SERIAL) &&
+                    (fold ? c->xi >= 0.125f : !merge_follows);
+    if (zc) mode = kStoreX;
     // everything in one kernel?  (decided below once the gradient layout is known)
     bool all = false;
     const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
@@ -572,6 +603,10 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     c->snap_valid = snap_step;
     c->y_in_snap = (mode == kStoreS);
     c->merged_in_step = fold;
+    c->zc = zc && !c->dry;
+    c->zc_recon = zc && fold;
+    c->zc_old_slot = (zc && fold) ? c->pending.front().slot : 0;
+    c->zc_xi = c->xi;
     c->mean_in_step = all;
     c->mean_deferred = false;
     c->snap_slot = (int)(c->n_launched % c->slots);

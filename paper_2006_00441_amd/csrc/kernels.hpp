@@ -335,6 +335,46 @@ k_mean_lds(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t r
     }
 }
 
+// Zero-copy snapshot with reconstruction.  When a step both launches an average and merges an older
+// one, the folded kernel leaves only the merged weights x' = y + om (A_old - y) = xi y + om A_old in
+// memory.  The average of the y is still recoverable from them, because the merge is affine and the
+// same for every replica:   mean_j y_j = (mean_j x'_j - om A_old) / xi .
+// So the mean kernel reads the live weights (no snapshot was stored) and undoes the merge on the
+// mean.  The subtraction cancels (operands ~|x|, result ~xi |x|), hence fp64 inside: what remains is
+// the fp32 rounding of the x'_j themselves, averaged over W and amplified by 1/xi.  Rows are split
+// over the NW wavefronts as in k_mean_lds (wave w takes rows w, w+NW, ...: any W).
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+template <int NW, bool RUNS>
+__global__ void __launch_bounds__(kWave * NW)
+k_mean_reconstruct(const v4f *__restrict__ X, const v4f *__restrict__ A_old, v4f *__restrict__ A_new,
+                   int64_t n4, int64_t row4, int W, double inv_w, double om, double inv_xi)
+{
+    __shared__ v4d part[NW][kWave];
+    __builtin_amdgcn_s_setprio(3);
+    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
+    const int64_t blk = RUNS ? ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7)
+                             : (int64_t)blockIdx.x;
+    const int64_t i = blk * kWave + l;
+    v4d acc = {0.0, 0.0, 0.0, 0.0};
+    if (i < n4) {
+        for (int j = w; j < W; j += NW) {
+            const v4f r = ld4<true>(X + (int64_t)j * row4 + i);
+            acc += __builtin_convertvector(r, v4d);
+        }
+    }
+    part[w][l] = acc;
+    __syncthreads();
+    if (w == 0 && i < n4) {
+        v4d m = part[0][l];
+#pragma unroll
+        for (int k = 1; k < NW; ++k) m += part[k][l];
+        const v4d a = __builtin_convertvector(ld4<false>(A_old + i), v4d);
+        const v4d y = (m * inv_w - om * a) * inv_xi;
+        st4<false>(A_new + i, __builtin_convertvector(y, v4f));
+    }
+}
+
 // Matrix layout, everything of one iteration in ONE pass: a wavefront owns a window of 64 columns of
 // ALL W rows; per lane it updates the W replicas of its column (local step), sums their new values
 // into the average that is launched at this step (MEAN) and folds the average launched d steps ago

@@ -30,7 +30,8 @@ class GpuRun:
     """
 
     def __init__(self, cfg: Config, layout: str = "arena", schedule: Optional[int] = None,
-                 device: str = "cuda:0", xi: Optional[float] = None, fusion: Optional[int] = None):
+                 device: str = "cuda:0", xi: Optional[float] = None, fusion: Optional[int] = None,
+                 snapshot: Optional[int] = None):
         import paper_2006_00441_amd as pkg
         self.pkg = pkg
         self.cfg = cfg
@@ -67,6 +68,8 @@ class GpuRun:
             self.opt.set_schedule(schedule)
         if fusion is not None:
             self.opt.set_fusion(fusion)
+        if snapshot is not None:
+            self.opt.set_snapshot(snapshot)
         self.g_ptrs = pkg.DaSGD.grad_pointers(self.g)
         self.k = 0
 
@@ -127,9 +130,9 @@ class GpuRun:
 
 def run_gpu(cfg: Config, steps: Optional[int] = None, layout: str = "arena", schedule: Optional[int] = None,
             observer: Optional[Callable[[int, GpuRun], None]] = None, idx: Optional[torch.Tensor] = None,
-            xi: Optional[float] = None, fusion: Optional[int] = None) -> np.ndarray:
+            xi: Optional[float] = None, fusion: Optional[int] = None, snapshot: Optional[int] = None) -> np.ndarray:
     """Run cfg on the GPU through the C ABI; returns the final weights [W, P] (or at idx)."""
-    run = GpuRun(cfg, layout=layout, schedule=schedule, xi=xi, fusion=fusion)
+    run = GpuRun(cfg, layout=layout, schedule=schedule, xi=xi, fusion=fusion, snapshot=snapshot)
     try:
         for k in range(cfg.steps if steps is None else steps):
             run.step()

@@ -59,6 +59,10 @@ def test_create_validates_arguments():
             o.set_fusion(f)
     for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL):
         o.set_fusion(f)
+    for m in (-1, 2):
+        with pytest.raises(DasgdError):
+            o.set_snapshot(m)
+    o.set_snapshot(pkg.SNAPSHOT_COPY); o.set_snapshot(pkg.SNAPSHOT_ZERO_COPY)
     o.destroy()
 
 

@@ -117,7 +117,7 @@ def test_fusion_levels_agree_bit_for_bit(tau, d, W, layout, pset):
     match the oracle."""
     import paper_2006_00441_amd as pkg
     cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
-    runs = [run_gpu(cfg, layout=layout, fusion=f)
+    runs = [run_gpu(cfg, layout=layout, fusion=f, snapshot=pkg.SNAPSHOT_COPY)
             for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL)]
     for r in runs[1:]:
         assert np.array_equal(runs[0], r)
@@ -141,10 +141,13 @@ def test_schedules_give_identical_results(pset, fusion):
     """Side-stream and single-stream schedules run the same kernels on the same data: bit-equal."""
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=8, steps=20, params=custom_param_set(SETS[pset]))
-    a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion)
-    b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion)
-    c = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP_FREE, fusion=fusion)
+    a = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion, snapshot=pkg.SNAPSHOT_COPY)
+    b = run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion, snapshot=pkg.SNAPSHOT_COPY)
+    c = run_gpu(cfg, schedule=pkg.SCHED_OVERLAP_FREE, fusion=fusion, snapshot=pkg.SNAPSHOT_COPY)
     assert np.array_equal(a, b) and np.array_equal(a, c)
+    # zero-copy snapshot (the default): same kernels in both schedules that allow it
+    assert np.array_equal(run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion),
+                          run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion))
 
 
 @pytest.mark.parametrize("pset", ["table", "matrix"])
@@ -205,10 +208,11 @@ def test_config_quadratic_full_every_step():
     both_oracles(cfg, run_gpu(cfg))
 
 
-@pytest.mark.parametrize("name,fusion", [("resnet50_w8", 2), ("resnet50_w8", 1), ("resnet50_w8", 0), ("resnet50_w8", 3),
-                                         ("resnet50_w16", 2), ("resnet50_w16", 3), ("bert_large_w4", 2),
-                                         ("bert_large_w4", 1), ("bert_large_w4", 3)])
-def test_config_full_size_sampled(name, fusion):
+@pytest.mark.parametrize("name,fusion,snapshot", [
+    ("resnet50_w8", 2, 1), ("resnet50_w8", 2, 0), ("resnet50_w8", 1, 0), ("resnet50_w8", 0, 0), ("resnet50_w8", 3, 0),
+    ("resnet50_w16", 2, 1), ("resnet50_w16", 2, 0), ("resnet50_w16", 3, 0),
+    ("bert_large_w4", 2, 1), ("bert_large_w4", 2, 0), ("bert_large_w4", 1, 0), ("bert_large_w4", 3, 0)])
+def test_config_full_size_sampled(name, fusion, snapshot):
     """Full-size run in the launch configuration the benchmark times; compared on sampled
     coordinates (all small tensors entirely, chunk boundaries, heads, tails, random elements):
     the method is elementwise across coordinates, so the oracle runs on exactly those."""
@@ -224,7 +228,7 @@ def test_config_full_size_sampled(name, fusion):
         if (k + 1) in checkpoints:
             errs[k + 1] = max_scaled_error(cfg, r.weights(idx), ref[k + 1], idx)
             print(f"[{name}] after step {k + 1}: scaled error {errs[k + 1]:.2e}", flush=True)
-    x_gpu = run_gpu(cfg, observer=obs, idx=idx, fusion=fusion)
+    x_gpu = run_gpu(cfg, observer=obs, idx=idx, fusion=fusion, snapshot=snapshot)
     assert max(errs.values()) <= TOL
     e32 = max_scaled_error(cfg, x_gpu, run_oracle(cfg, "f32", idx=idx), idx)
     print(f"[{name}] final vs f32 oracle {e32:.2e} on {idx.numel()} sampled coordinates", flush=True)
@@ -358,3 +362,51 @@ def test_profile_counts_and_times_launches():
     assert total == 2 * cfg.steps                                          # one step kernel + one mean per step
     run.opt.profile(0)
     run.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# zero-copy snapshot (the default where it applies)
+@pytest.mark.parametrize("tau,d,W,xi", [(1, 1, 4, 0.25), (1, 2, 8, 0.25), (1, 4, 4, 0.5), (2, 2, 3, 0.125), (2, 4, 16, 0.25),
+                                        (1, 2, 5, 0.9), (1, 3, 1, 0.25), (1, 2, 8, 1.0)])
+@pytest.mark.parametrize("layout,pset", [("arena", "matrix"), ("arena_padded", "table"), ("arena_padded", "matrix_even")])
+def test_zero_copy_snapshot_with_reconstruction(tau, d, W, xi, layout, pset):
+    """Steps that launch an average and merge an older one at once (d a multiple of tau): no snapshot
+    is stored, the mean of the y is recovered from the merged weights.  Rounding differs from the
+    copy path in the last bits; both stay within the tolerance of the oracle."""
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=tau, d=d, W=W, xi=xi, steps=40, params=custom_param_set(SETS[pset]))
+    run = GpuRun(cfg, layout=layout)
+    run.opt.profile(1, 1000)
+    for _ in range(cfg.steps):
+        run.step()
+    x = run.weights()
+    if run.opt.layout()[1] - cfg.P < 32:      # bound as a matrix (one replica of odd length is not: no stride to see)
+        assert run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2] > 0          # the path under test really ran
+        assert run.opt.profile_read(pkg.K_LOCAL_STEP_SNAP)[2] == 0 and run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] == 0
+    else:
+        assert W == 1 and pset == "table"
+    run.close()
+    both_oracles(cfg, x)
+    assert max_scaled_error(cfg, x, run_gpu(cfg, layout=layout, snapshot=pkg.SNAPSHOT_COPY)) <= 0.5 * TOL
+
+
+@pytest.mark.parametrize("tau,d,W", [(4, 2, 16), (3, 1, 5), (5, 4, 8)])
+def test_zero_copy_snapshot_is_exact_without_coinciding_merge(tau, d, W):
+    """d not a multiple of tau: no step both launches and merges, the mean reads y straight from x:
+    identical bits to the copy path."""
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=tau, d=d, W=W, steps=4 * tau + d + 3, params=custom_param_set(SETS["matrix"]))
+    assert np.array_equal(run_gpu(cfg), run_gpu(cfg, snapshot=pkg.SNAPSHOT_COPY))
+
+
+def test_zero_copy_falls_back_to_the_copy_for_small_xi():
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=1, d=2, W=4, xi=0.05, steps=12, params=custom_param_set(SETS["matrix"]))
+    run = GpuRun(cfg)
+    run.opt.profile(1, 1000)
+    for _ in range(cfg.steps):
+        run.step()
+    x = run.weights()
+    assert run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2] == 0 and run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] > 0
+    run.close()
+    assert np.array_equal(x, run_gpu(cfg, snapshot=pkg.SNAPSHOT_COPY))
