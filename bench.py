@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the DaSGD per-step parameter pipeline on one MI355X.
 
-A step is one pass of the whole hot path over all W replicas: local step (with the fused snapshot
-store), launch of the W-way mean on the side stream, and the delayed merge.  The default workload
+A step is one pass of the whole hot path over all W replicas: local step, launch of the W-way mean
+on the side stream, and the delayed merge (folded into the local-step kernel by default).  The default workload
 is the ResNet-50-shaped set with W=8, tau=1, d=2 (every step launches an average and merges the one
 launched two steps earlier).  Inputs (weights, momentum, gradients) are resident in HBM before the
 timed region starts.  Prints ONE JSON line.
