@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+ALU_STANDIN_ITERS = 18000      # loop trips of the ALU-bound stand-in (about the duration of the 8192^3 GEMM)
 PROFILE_EVERY = 8              # per-kernel event timing samples one launch in 8 (an event pair costs ~5 us)
 
 
@@ -47,7 +48,9 @@ class Bench:
     layout = "matrix"      # "matrix": W x P arenas, rows 128-byte aligned (arithmetic addressing);
                            # "separate": one allocation per tensor (chunk-table addressing)
 
-    def __init__(self, cfg, schedule: int, gemm: bool = False):
+    def __init__(self, cfg, schedule: int, gemm=False):
+        """gemm: False = no forward/backward stand-in; True = one bf16 8192^3 torch.matmul per step;
+        "alu" = the register-light ALU-bound stand-in kernel of bench_standin.hip."""
         import torch
         import workloads as wl
         import paper_2006_00441_amd as pkg
@@ -71,7 +74,13 @@ class Bench:
                 q = wl.QuadraticProblem.build(cfg, dev)
                 for j in range(W):
                     self.g[j].copy_(q.grad(self.x[j], 0, j))
-            if gemm:   # forward/backward stand-in: bf16 GEMM 8192^3 from seeded N(0,1) data
+            if gemm == "alu":
+                import ctypes
+                self.alu = ctypes.CDLL(os.path.join(ROOT, "bench_standin.so"))
+                self.alu.bench_alu_standin.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+                self.alu_blocks, self.alu_iters = 1024, ALU_STANDIN_ITERS
+                self.alu_out = torch.empty(self.alu_blocks * 256, device=dev)
+            elif gemm:   # forward/backward stand-in: bf16 GEMM 8192^3 from seeded N(0,1) data
                 ii = torch.arange(8192 * 8192, device=dev, dtype=torch.int64)
                 self.ga = wl.standard_normal(wl.stream_key(cfg.seed, 101), ii).view(8192, 8192).to(torch.bfloat16)
                 self.gb = wl.standard_normal(wl.stream_key(cfg.seed, 102), ii).view(8192, 8192).to(torch.bfloat16)
@@ -99,7 +108,10 @@ class Bench:
         self.main.synchronize()
 
     def step(self):
-        if self.gemm:
+        if self.gemm == "alu":
+            rc = self.alu.bench_alu_standin(self.alu_out.data_ptr(), self.alu_blocks, self.alu_iters, self.main.cuda_stream)
+            assert rc == 0, rc
+        elif self.gemm:
             with self.torch.cuda.stream(self.main):
                 self.torch.matmul(self.ga, self.gb, out=self.gc)
         self.opt.step(self.g_ptrs if self.first else None)
@@ -186,7 +198,8 @@ def overlap_study(cfg, steps: int, warmup: int, gemm: bool):
     t_avg = t["S0_serial"] - t["F_no_average"]
     hidden = (t["S0_serial"] - t["S1_overlap"]) / t_avg if t_avg > 0 else None
     hidden_free = (t["S0_serial"] - t["S1_overlap_free"]) / t_avg if t_avg > 0 else None
-    return {"gemm_8192_bf16_per_step": gemm, "ms_per_step": {k: round(v, 4) for k, v in t.items()},
+    return {"stand_in": {False: "none", True: "bf16 GEMM 8192^3 (torch.matmul)", "alu": "ALU-bound kernel, 4 waves/SIMD, 16 VGPRs"}[gemm],
+            "ms_per_step": {k: round(v, 4) for k, v in t.items()},
             "averaging_ms": round(t_avg, 4), "hidden_frac": None if hidden is None else round(hidden, 4),
             "hidden_frac_overlap_free": None if hidden_free is None else round(hidden_free, 4),
             "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4)}
@@ -369,6 +382,8 @@ def main() -> int:
         k = max(20, min(args.steps, 100))
         out["overlap"] = {"hbm_bound_steps_only": overlap_study(cfg, k, 10, gemm=False),
                           "with_compute_stand_in": overlap_study(cfg, k, 10, gemm=True)}
+        if os.path.exists(os.path.join(ROOT, "bench_standin.so")):
+            out["overlap"]["with_register_light_stand_in"] = overlap_study(cfg, k, 10, gemm="alu")
         if cfg.kind == "external" and cfg.P % 4 == 0 and args.layout == "matrix":
             out["algorithms"] = compare_algorithms(cfg, 40, 8)
     if not args.only_timed and args.layout == "matrix" and args.fusion is None:
