@@ -123,7 +123,8 @@ enum {
  * Returns NULL on invalid arguments or allocation failure. */
 dasgd_ctx *dasgd_create(int W, int64_t P, int d, int tau, float lr, float momentum, float wd);
 
-/* Set xi in [0,1] (Eq. 2: weight of the local value at a merge).  Takes effect from the next merge. */
+/* Set xi in [0,1] (Eq. 2: weight of the local value at a merge).  Takes effect from the next local
+ * step (whose kernel may already apply that step's merge); call it between whole iterations. */
 int dasgd_set_xi(dasgd_ctx *ctx, float xi);
 
 /* Set the learning rate (caller-side schedules; the paper's runs use a one-cycle policy,
@@ -172,15 +173,14 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
 
 /* Local step k -> k+1 on every replica (Eq. 2, first branch, with the optimiser of Section 4.1):
  *     g' = g + wd x ;  v <- momentum v + g' ;  x <- x - lr v
- * one fused kernel over all replicas and tensors on main_stream.  When (k+1) mod tau == 0 the
- * same kernel also stores the new weights into a snapshot slot for the average that
- * dasgd_average_begin will launch.  When, in addition, a merge is due at this same step, the
- * kernel stores the new weights ONLY into the snapshot and dasgd_merge reads them from there:
- * x then holds the finished x_{k+1} only after this step's dasgd_merge (which the caller has to
- * issue before the next local step anyway).  At the default fusion level a merge due at this step
- * (d > 0) is applied by this same kernel, after a device-side wait for that average, with the xi
- * in effect now; dasgd_merge then only retires the average.  In every case x holds x_{k+1} once
- * the calls of the canonical loop for this step have been issued, and not necessarily before.
+ * one fused kernel over all replicas and tensors on main_stream.  What else that kernel does depends
+ * on the step and on the settings (DASGD_FUSE_*, DASGD_SNAPSHOT_*): when (k+1) mod tau == 0 it may
+ * store the new weights into a snapshot slot for the average that dasgd_average_begin will launch;
+ * when a merge is due at this same step (and d > 0) it applies that merge in the same pass, after a
+ * device-side wait for the average, with the xi in effect now -- dasgd_merge then only retires the
+ * average; at lower fusion levels it may leave the new weights only in the snapshot for
+ * dasgd_merge to pick up.  What is guaranteed: x holds x_{k+1} once all calls of the canonical loop
+ * for this step have been issued (in stream order), and not necessarily between them.
  *   g   [W * n_tensors] host array of device pointers (same order and shapes as x), read only;
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
  *       pointers of the previous call (the table is re-uploaded only when it changes).
@@ -193,9 +193,10 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
 int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
 
-/* Launch the average of the weights as they were right after the latest local step (Eq. 2's
- * summand x - eta g; matrix form (X - eta G) J in the appendix): A = (1/W) sum_j snapshot_j, on
- * side_stream after main_stream's local step, occupying a ring slot until merged.  When a merge of
+/* Launch the average of the weights as they were right after the latest local step and before any
+ * merge (Eq. 2's summand x - eta g; matrix form (X - eta G) J in the appendix): A = (1/W) sum_j y_j,
+ * on side_stream after main_stream's local step, occupying a ring slot until merged.  The y_j are
+ * read from the snapshot, or from the live weights (DASGD_SNAPSHOT_ZERO_COPY).  When a merge of
  * an older average is due at this same step, the launch is held back until that merge has been
  * enqueued (the mean has d steps of slack, the merge none), so that the mean runs beside the
  * caller's next forward/backward pass rather than beside the merge.
