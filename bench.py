@@ -141,6 +141,26 @@ class Bench:
         self.torch.cuda.empty_cache()
 
 
+def copy_ceiling(cfg):
+    """Bandwidth of a plain device-to-device copy of W*P floats on this machine (read + write bytes over
+    time): what a streaming kernel can reach in practice, beside the vendor peak."""
+    import torch
+    src = torch.zeros(cfg.W, cfg.P, device="cuda:0"); dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2.0 * cfg.W * cfg.P * 4 / (ms * 1e-3) / 1e9
+
+
 def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
     """The headline measurement: overlap schedule, per-kernel event timing live in the timed region."""
     import paper_2006_00441_amd as pkg
@@ -378,6 +398,10 @@ def main() -> int:
     step_bytes = sum(k["algorithmic_bytes"] * k["launches"] for k in kernels.values()) / args.steps
     out["whole_step"] = {"algorithmic_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                          "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if not args.only_timed:
+        ceil_gbs = copy_ceiling(cfg)
+        out["roofline"]["copy_ceiling_GBps"] = round(ceil_gbs, 1)
+        out["roofline"]["frac_of_copy_ceiling"] = round(d["GBps"] / ceil_gbs, 4)
     if not args.only_timed and not args.no_overlap_study:
         k = max(20, min(args.steps, 100))
         out["overlap"] = {"hbm_bound_steps_only": overlap_study(cfg, k, 10, gemm=False),
