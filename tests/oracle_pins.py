@@ -241,6 +241,28 @@ def check_delayed_self_merge(lib):
     o.close()
 
 
+def check_matrix_form(lib):
+    """The appendix's matrix form for plain SGD local steps:
+        X_{k+1} = xi (X_k - eta G_k) + (1 - xi) (X_{k-d} - eta G_{k-d}) J   when (k+1-d) mod tau == 0,
+        X_{k+1} = X_k - eta G_k                                              otherwise,
+    with J = 1 1^T / M applied as a matrix product (columns = workers).  Y_k = X_k - eta G_k is formed
+    here from the oracle's X_k and the gradients it was fed."""
+    r = _rng(12)
+    for (tau, d, xi, M) in ((1, 2, 0.25, 8), (4, 2, 0.25, 4), (3, 3, 0.6, 5), (2, 1, 0.0, 3)):
+        P, K, eta = 7, 6 * tau + d, 0.05
+        J = np.full((M, M), 1.0 / M)
+        o = oracle.Oracle(M, P, d, tau, eta, 0.0, 0.0, r.standard_normal(P), xi=xi, dtype="f64", lib=lib)
+        Y = []
+        for k in range(K):
+            G = r.standard_normal((M, P))
+            Y.append(o.x.T.copy() - oracle.f32(eta) * G.T)            # dim x M, as in the paper
+            o.step(G)
+            merge = (k + 1 - d) % tau == 0 and k - d >= tau - 1
+            want = oracle.f32(xi) * Y[k] + (1 - oracle.f32(xi)) * (Y[k - d] @ J) if merge else Y[k]
+            np.testing.assert_allclose(o.x.T, want, rtol=1e-12, atol=1e-13, err_msg=f"tau={tau} d={d} k={k}")
+        o.close()
+
+
 def check_xi_contraction(lib):
     """At a merge every replica moves toward a common point: the spread around the replica mean
     is multiplied by exactly xi, and the replica mean becomes xi ybar_k + (1-xi) A_{k-d}
@@ -363,6 +385,7 @@ ALL_CHECKS = [
     check_merge_steps,
     check_identical_replicas,
     check_delayed_self_merge,
+    check_matrix_form,
     check_xi_contraction,
     check_quadratic_closed_form,
     check_mean,

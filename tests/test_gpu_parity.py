@@ -410,3 +410,18 @@ def test_zero_copy_falls_back_to_the_copy_for_small_xi():
     assert run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2] == 0 and run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] > 0
     run.close()
     assert np.array_equal(x, run_gpu(cfg, snapshot=pkg.SNAPSHOT_COPY))
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 5, 63, 64, 65, 252, 255, 256, 257, 260, 4095, 4096, 4097, 8192])
+@pytest.mark.parametrize("W,layout", [(1, "arena"), (2, "arena"), (8, "arena"), (3, "arena_padded"), (8, "arena_padded"), (4, "separate")])
+def test_tiny_and_boundary_sizes(P, W, layout):
+    """One tensor of P elements around every boundary the kernels have (one 128-bit element, one
+    64-element block, one 4096-element chunk, rows shorter than a block), all paths, bit-equal across
+    the fusion levels and against the oracle."""
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=1, d=1, W=W, steps=7, params=wl.flat_param_set(P))
+    ref = run_gpu(cfg, layout=layout, fusion=pkg.FUSE_NONE, snapshot=pkg.SNAPSHOT_COPY)
+    for f in (pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL):
+        assert np.array_equal(ref, run_gpu(cfg, layout=layout, fusion=f, snapshot=pkg.SNAPSHOT_COPY)), f
+    assert max_scaled_error(cfg, ref, run_oracle(cfg, "f64")) <= TOL
+    assert max_scaled_error(cfg, run_gpu(cfg, layout=layout), run_oracle(cfg, "f64")) <= TOL      # defaults (zero-copy)
