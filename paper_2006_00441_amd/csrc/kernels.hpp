@@ -1,20 +1,23 @@
 // Device code of the DaSGD parameter pipeline for gfx950 (CDNA4, 64-wide wavefronts).
 //
-// All kernels are pure streaming passes bound by HBM bandwidth (<= 0.3 flop per byte), so the
-// design is about memory traffic only: 128-bit accesses, every byte touched once, non-temporal
-// hints on everything that streams, no LDS, no MFMA.
+// All kernels are streaming passes bound by HBM bandwidth (<= 0.3 flop per byte), so the design is
+// about memory traffic only: 128-bit accesses, every byte touched once, non-temporal hints on
+// everything that streams, whole aligned kilobytes per wavefront, no MFMA (nothing is a contraction).
 //
 //   local step   x, v, g -> x, v [, snapshot]        (paper Eq. 2, first branch; Section 4.1)
-//   mean         snapshot rows -> average             ((X - eta G) J of the matrix form, appendix)
-//   merge        y, average -> x                      (Eq. 2, second branch)
+//   mean         rows of y (or of merged x) -> A      ((X - eta G) J of the matrix form, appendix)
+//   merge        y, A -> x                            (Eq. 2, second branch)
+//   and the fused forms: local step + merge; local step + mean + merge.
 //
-// Two families.  The "matrix" kernels (k_*_flat) serve the layout the paper's matrix form suggests:
-// X, V, G are W x P row-major matrices (one row per replica, rows back to back).  They address by
-// pure arithmetic and run one 64-lane wavefront per workgroup with one 128-bit access per lane per
-// array: measured on MI355X this shape sustains the highest HBM throughput (short-lived single-wave
-// workgroups keep the memory system evenly fed; anything that delays a wave's first load -- a
-// descriptor fetch, a larger workgroup -- costs bandwidth).  The "table" kernels (k_local_step,
-// k_merge) serve arbitrary per-tensor pointers through a chunk table.
+// Two families.  The "matrix" kernels (k_*_flat, k_mean*) serve the layout the paper's matrix form
+// suggests: X, V, G are W x P row-major matrices (one row per replica, one row stride).  They
+// address by pure arithmetic and run one 64-lane wavefront per workgroup with one 128-bit access per
+// lane per array: measured on MI355X this shape sustains the highest HBM throughput (short-lived
+// single-wave workgroups keep the memory system evenly fed; anything that delays a wave's first
+// load -- a descriptor fetch, a larger workgroup -- costs bandwidth).  The one exception is the mean,
+// whose many loads per column are better split over the wavefronts of a workgroup and combined
+// through LDS.  The "table" kernels (k_local_step, k_merge) serve arbitrary per-tensor pointers
+// through a chunk table.
 #pragma once
 
 #include <hip/hip_runtime.h>
