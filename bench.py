@@ -9,6 +9,7 @@ timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_w8|resnet50_w16|bert_large_w4|quadratic]
                     [--no-cpu-baseline] [--no-overlap-study] [--only-timed]
+    python bench.py --sweep      # xi / d / tau study on the quadratic instead (its own JSON line)
 """
 from __future__ import annotations
 
@@ -279,6 +280,92 @@ def compare_algorithms(cfg, steps: int, warmup: int):
             "note": "each step = bf16 8192^3 GEMM stand-in + the schedule's parameter work, W=%d replicas" % cfg.W}
 
 
+def quadratic_period_maps(a, lr: float, momentum: float, xi: float, d: int):
+    """Linear maps of the replica-mean error on the noise-free quadratic (curvature + weight decay = a
+    per coordinate; Eq. 2 with heavy-ball momentum).  State per coordinate: (e, vbar, ytilde_{k-1}, ...,
+    ytilde_{k-d}) with e the distance of the replica mean from the fixed point.  Returns (plain step,
+    merge step), each of shape [len(a), d+2, d+2], fp64."""
+    import numpy as np
+    a = np.asarray(a, dtype=np.float64)
+    n = d + 2
+    y = np.zeros((a.size, n)); y[:, 0] = 1.0 - lr * a; y[:, 1] = -lr * momentum   # ytilde from (e, vbar)
+    plain = np.zeros((a.size, n, n))
+    plain[:, 0] = y
+    plain[:, 1, 0] = a; plain[:, 1, 1] = momentum
+    if d:
+        plain[:, 2] = y
+        for i in range(3, n):
+            plain[:, i, i - 1] = 1.0
+    merge = plain.copy()
+    if d:
+        merge[:, 0] = xi * y
+        merge[:, 0, n - 1] += 1.0 - xi
+    return plain, merge
+
+
+def sweep_quadratic(K0: int = 48, K1: int = 144):
+    """Parameter study on the quadratic (xi, d and tau ranges of the paper's Fig. 6(d), 6(e) and its tau
+    advice, Section 4): the HIP path runs the noise-free problem and the decay rate of the replica mean's
+    distance to the fixed point between steps K0 and K1 is set beside the rate the linear recurrence
+    predicts for the same window and beside its asymptote, the spectral radius of one period's map."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2006_00441_amd as pkg
+    base = wl.get_config("quadratic")
+    dev = torch.device("cuda:0")
+    grid = [("xi", dict(xi=x, tau=4, d=2)) for x in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0)]
+    grid += [("d", dict(xi=0.25, tau=8, d=d)) for d in range(8)]
+    grid += [("tau", dict(xi=0.25, tau=t, d=1)) for t in (1, 2, 4, 8, 16, 48)]
+    main, side = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    rows = []
+    for axis, kw in grid:
+        cfg = base.scaled(**kw)
+        W, P, tau, d, xi = cfg.W, cfg.P, cfg.tau, cfg.d, cfg.xi
+        with torch.cuda.stream(main):
+            q = wl.QuadraticProblem.build(cfg, dev, noise=False)
+            x = torch.zeros(W, P, device=dev); v = torch.zeros_like(x); g = torch.empty_like(x)
+            a32 = q.h.double() + float(np.float32(cfg.wd))
+            wstar = q.h.double() * q.c.double().mean(0) / a32
+        main.synchronize()
+        opt = pkg.DaSGD(W, P, d, tau, cfg.lr, cfg.momentum, cfg.wd, xi=xi)
+        ws = opt.bind_tensors([[x[j]] for j in range(W)], [[v[j]] for j in range(W)], main, side)
+        gp = pkg.DaSGD.grad_pointers([[g[j]] for j in range(W)])
+        sel = torch.arange(0, P, 64, device=dev)     # both sides look at every 64th coordinate
+        err = {}
+        for k in range(K1):
+            with torch.cuda.stream(main):
+                torch.mul(x - q.c, q.h, out=g)       # gradient at each replica's current iterate
+            opt.step(gp if k == 0 else None)
+            if k + 1 in (K0, K1):
+                with torch.cuda.stream(main):
+                    err[k + 1] = float((x[:, sel].double().mean(0) - wstar[sel]).norm())
+        main.synchronize()
+        opt.destroy()
+        a = a32[sel].cpu().numpy()
+        f = lambda z: float(np.float32(z))
+        plain, merge = quadratic_period_maps(a, f(cfg.lr), f(cfg.momentum), f(xi), d)
+        st = np.zeros((a.size, d + 2)); st[:, 0] = -wstar[sel].cpu().numpy()        # w0 = 0
+        pred = {}
+        for k in range(K1):
+            is_merge = (k + 1 - d) % tau == 0 and k - d >= tau - 1
+            st = np.einsum("pij,pj->pi", merge if is_merge else plain, st)
+            if k + 1 in (K0, K1):
+                pred[k + 1] = float(np.linalg.norm(st[:, 0]))
+        period = np.broadcast_to(np.eye(d + 2), plain.shape).copy()
+        for k in range(d, d + tau):                                       # one period in steady state
+            period = np.einsum("pij,pjk->pik", merge if (k + 1 - d) % tau == 0 else plain, period)
+        rho = float(np.abs(np.linalg.eigvals(period)).max() ** (1.0 / tau))
+        rate = lambda e: (e[K1] / e[K0]) ** (1.0 / (K1 - K0))
+        rows.append({"axis": axis, "xi": xi, "tau": tau, "d": d,
+                     "error_at_K0": err[K0], "error_at_K1": err[K1],
+                     "measured_rate_per_step": round(rate(err), 6), "recurrence_rate_per_step": round(rate(pred), 6),
+                     "predicted_error_at_K1": pred[K1], "spectral_radius_per_step": round(rho, 6)})
+        del ws
+    return {"sweep": "noise-free quadratic, W=4, P=2^20, lr 0.1, momentum 0.9, wd 1e-4; error = L2 distance of the "
+                     "replica mean from the fixed point over every 64th coordinate", "K0": K0, "K1": K1, "dtype": "f32", "rows": rows}
+
+
 def cpu_baseline(cfg, budget_s: float = 12.0):
     """The CPU oracle (fp32 variant, as it stands) timed on this machine's host cores on a bounded number
     of steps of the same workload at full size."""
@@ -348,6 +435,8 @@ def main() -> int:
     ap.add_argument("--layout", default="matrix", choices=["matrix", "separate"],
                     help="matrix: x, v, g as W x P arenas (default); separate: one allocation per tensor")
     ap.add_argument("--fusion", type=int, default=None, help="fusion level 0..3 (default: the library's)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark: xi / d / tau study on the quadratic, one JSON line")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run 5 plain torch copies of W*P floats (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -364,6 +453,9 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU implementation of this path", file=sys.stderr)
         return 2
     pkg.lib()
+    if args.sweep:
+        print(json.dumps(sweep_quadratic()))
+        return 0
     Bench.layout = args.layout
     Bench.fusion = args.fusion
     cfg = wl.get_config(args.workload)

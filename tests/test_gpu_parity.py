@@ -425,3 +425,26 @@ def test_tiny_and_boundary_sizes(P, W, layout):
         assert np.array_equal(ref, run_gpu(cfg, layout=layout, fusion=f, snapshot=pkg.SNAPSHOT_COPY)), f
     assert max_scaled_error(cfg, ref, run_oracle(cfg, "f64")) <= TOL
     assert max_scaled_error(cfg, run_gpu(cfg, layout=layout), run_oracle(cfg, "f64")) <= TOL      # defaults (zero-copy)
+
+
+# ------------------------------------------------------------------------------------------------
+# the HIP path against the closed form of the noise-free quadratic (no oracle time-stepping involved)
+@pytest.mark.parametrize("xi", [0.0, 0.25, 0.9])
+@pytest.mark.parametrize("tau,d", [(1, 0), (1, 1), (1, 3), (4, 2), (3, 7), (8, 5)])
+def test_quadratic_closed_form_on_gpu(xi, tau, d):
+    """Replica mean after K steps = matrix-power evolution of the linear recurrence that Eq. 2 gives on
+    a diagonal quadratic (fp64, no replicas, no FIFO)."""
+    from oracle_pins import quadratic_mean_closed_form
+    K = 60
+    cfg = wl.get_config("quadratic").scaled(params=wl.flat_param_set(4096 + 8), tau=tau, d=d, xi=xi, steps=K)
+    run = GpuRun(cfg)
+    run.quad = wl.QuadraticProblem.build(cfg, run.dev, noise=False)
+    for _ in range(K):
+        run.step()
+    got = run.weights().astype(np.float64).mean(axis=0)
+    h = run.quad.h.double().cpu().numpy()
+    cbar = run.quad.c.double().mean(0).cpu().numpy()
+    want, wstar = quadratic_mean_closed_form(h, cbar, np.zeros(cfg.P), K, tau, d, cfg.lr, cfg.momentum, cfg.wd, xi)
+    scale = max(np.sqrt((want ** 2).mean()), 1e-30)
+    assert np.abs(got - want).max() <= TOL * scale
+    run.close()
