@@ -190,6 +190,31 @@ def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
     return wall, ev_ms, kernels
 
 
+def repeats(cfg, n: int = 5, steps: int = 50, warmup: int = 10, gemm=False):
+    """Spread of the step time: n back-to-back timings of `steps` steps each (main-stream events)."""
+    import paper_2006_00441_amd as pkg
+    b = Bench(cfg, pkg.SCHED_OVERLAP, gemm=gemm)
+    ms = []
+    for r in range(n):
+        _, ev = b.run(steps, warmup if r == 0 else 0)
+        ms.append(ev / steps)
+    b.close()
+    ms.sort()
+    return {"steps_each": steps, "ms_per_step": [round(m, 5) for m in ms], "median_ms_per_step": round(ms[n // 2], 5)}
+
+
+def local_step_alone(cfg, steps: int, warmup: int):
+    """Local step only (tau so large that no average is ever due): 20 B per replica-parameter."""
+    import paper_2006_00441_amd as pkg
+    b = Bench(cfg.scaled(tau=1 << 30), pkg.SCHED_OVERLAP)
+    wall, _ = b.run(steps, warmup)
+    b.close()
+    rp = cfg.W * cfg.P
+    gbs = 20.0 * rp * steps / wall / 1e9
+    return {"ms_per_step": round(wall / steps * 1e3, 5), "value": rp * steps / wall, "unit": "replica-params/s",
+            "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
 def fusion_all_region(cfg, steps: int, warmup: int):
     """The same workload with the mean folded into the local-step kernel as well (fusion level 3: one
     kernel per step, nothing on the side stream).  Reported beside the headline, never as it."""
@@ -512,6 +537,9 @@ def main() -> int:
             out["overlap"]["with_register_light_stand_in"] = overlap_study(cfg, k, 10, gemm="alu")
         if cfg.kind == "external" and cfg.P % 4 == 0 and args.layout == "matrix":
             out["algorithms"] = compare_algorithms(cfg, 40, 8)
+    if not args.only_timed:
+        out["repeats"] = repeats(cfg, gemm=(cfg.name == "overlap"))
+        out["local_step_alone"] = local_step_alone(cfg, args.steps, args.warmup)
     if not args.only_timed and args.layout == "matrix" and args.fusion is None:
         out["fusion_all"] = fusion_all_region(cfg, args.steps, args.warmup)
     if not args.only_timed and not args.no_cpu_baseline:
