@@ -160,7 +160,8 @@ size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t 
  *   main_stream, side_stream   hipStream_t handles; local step and merge run on main_stream,
  *              the W-way mean on side_stream.  Must be different streams of equal priority.
  * Copies the tables to the device and clears snapshots/averages (blocks until done).
- * Errors: EINVAL, ENOMEM (workspace too small), ESTATE (already bound), EHIP. */
+ * Errors: EINVAL, ENOMEM (workspace too small), ESTATE (already bound, or an earlier bind of this
+ * context failed with EHIP: destroy it and create a new one), EHIP. */
 int dasgd_bind(dasgd_ctx *ctx, int n_tensors, const int64_t *numel,
                float *const *x, float *const *v,
                void *workspace, size_t workspace_bytes,

@@ -326,6 +326,7 @@ static int bind_common(dasgd_ctx *c, int n_tensors, const int64_t *numel)
 {
     if (!shapes_ok(c, n_tensors, numel)) return DASGD_EINVAL;
     if (c->bound) return DASGD_ESTATE;
+    if (c->g_pinned || !c->snap_done.empty()) return DASGD_ESTATE;     // an earlier bind failed half-way
     return DASGD_OK;
 }
 
@@ -398,10 +399,10 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     }
     HIPCHK(c, hipStreamSynchronize(c->main_s));
 
+    c->snap_done.assign(c->slots, nullptr);
+    c->avg_done.assign(c->slots, nullptr);
     HIPCHK(c, hipHostMalloc(&c->g_pinned, sizeof(void *) * rows * kGTables, hipHostMallocDefault));
     for (int b = 0; b < kGTables; ++b) HIPCHK(c, hipEventCreateWithFlags(&c->g_ev[b], hipEventDisableTiming));
-    c->snap_done.resize(c->slots);
-    c->avg_done.resize(c->slots);
     for (int s = 0; s < c->slots; ++s) {
         HIPCHK(c, hipEventCreateWithFlags(&c->snap_done[s], hipEventDisableTiming));
         HIPCHK(c, hipEventCreateWithFlags(&c->avg_done[s], hipEventDisableTiming));

@@ -448,3 +448,44 @@ def test_quadratic_closed_form_on_gpu(xi, tau, d):
     scale = max(np.sqrt((want ** 2).mean()), 1e-30)
     assert np.abs(got - want).max() <= TOL * scale
     run.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# the largest problem the 32-bit-index kernels accept (W * row stride / 4 + 64 < 2^31)
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("P", [2**30 - 64, 2**30])
+def test_maximum_size_of_the_matrix_kernels(P):
+    """W = 8 replicas of 2^30 - 64 parameters: 34 GB per arena, 180 GB in all, the largest problem the
+    32-bit-index kernels take; at 2^30 the library must switch the folded step and the merge to the
+    chunk-table kernels (64-bit offsets).  Checked on sampled coordinates, which include both ends of
+    every tensor and of the arena."""
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 215 * 2**30:
+        pytest.skip(f"needs 215 GiB of free device memory, {free / 2**30:.0f} GiB available")
+    ps = custom_param_set([2**29, P - 2**29 - 8192, 8192 - 4, 4], "max32")
+    assert ps.P == P
+    cfg = wl.Config("max32", ps, W=8, tau=1, d=1, lr=0.05, momentum=0.9, wd=1e-3, steps=4, seed=3,
+                    init="normal", init_std=0.02, grad_std=1e-3)
+    idx = sample_indices(cfg)
+    ref = run_oracle(cfg, "f64", idx=idx)
+    run = GpuRun(cfg)
+    assert run.opt.layout()[1] == cfg.P              # matrix layout taken, row stride = P
+    run.opt.profile(1, 64)
+    for _ in range(cfg.steps):
+        run.step()
+    got = run.weights(idx)
+    timed = {name: run.opt.profile_read(kid)[1] for kid, name in pkg_kernel_names().items()}
+    print("[max32] kernels:", {k: v for k, v in timed.items() if v}, flush=True)
+    assert timed["step_merge"] == cfg.steps - 1 and timed["mean_reconstruct"] == cfg.steps - 1
+    err = max_scaled_error(cfg, got, ref, idx)
+    print(f"[max32] scaled error on {idx.numel()} sampled coordinates: {err:.2e}", flush=True)
+    assert err <= TOL
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+
+
+def pkg_kernel_names():
+    import paper_2006_00441_amd as pkg
+    return pkg.KERNEL_NAMES
