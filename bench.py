@@ -62,7 +62,7 @@ class Bench:
         self.side = torch.cuda.Stream(dev)
         W, P = cfg.W, cfg.P
         off, n = cfg.params.offsets, cfg.params.n_tensors
-        ld = (P + 31) // 32 * 32            # row stride: rows 128-byte aligned to each other
+        ld = (P + 255) // 256 * 256          # row stride: rows 1 KiB aligned to each other
         with torch.cuda.stream(self.main):
             w0 = wl.init_weights(cfg, dev)
             self._full = [torch.zeros(W, ld, device=dev) for _ in range(3)]
@@ -106,6 +106,7 @@ class Bench:
             self.opt.set_fusion(Bench.fusion)
         self.g_ptrs = pkg.DaSGD.grad_pointers(gs)
         self.first = True
+        self.steps_done = 0
         self.main.synchronize()
 
     def step(self):
@@ -117,12 +118,30 @@ class Bench:
                 self.torch.matmul(self.ga, self.gb, out=self.gc)
         self.opt.step(self.g_ptrs if self.first else None)
         self.first = False
+        self.steps_done += 1
+
+    def settle(self, limit: int = 512) -> int:
+        """Untimed steps beyond the warm-up until the library has finished measuring its band lengths
+        (a warm-up matter, like any autotuning): returns how many were needed."""
+        extra = 0
+        for _ in range(max(0, min(self.cfg.d + self.cfg.tau + 1, 64) - self.steps_done)):    # reach the first merge
+            self.step()
+            extra += 1
+        self.torch.cuda.synchronize()
+        while self.opt.bands_in_flux() and extra < limit:
+            for _ in range(self.cfg.tau):
+                self.step()
+            extra += self.cfg.tau
+            self.torch.cuda.synchronize()
+        return extra
 
     def run(self, steps: int, warmup: int):
         """Returns (wall seconds for `steps` steps, main-stream event milliseconds)."""
         torch = self.torch
         for _ in range(warmup):
             self.step()
+        if warmup:
+            self.settle()
         e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -178,6 +197,7 @@ def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
     b = Bench(cfg, pkg.SCHED_OVERLAP, gemm=gemm)
     for _ in range(warmup):
         b.step()
+    tuning_steps = b.settle()
     b.opt.profile(PROFILE_EVERY, 4 * steps + 16)
     wall, ev_ms = b.run(steps, 0)
     kernels = {}
@@ -186,8 +206,11 @@ def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
         if n:
             kernels[name] = {"launches": launched, "timed_launches": n, "avg_ms": ms / n}
     b.opt.profile(0)
+    tuning = {"extra_untimed_steps": tuning_steps,
+              "log2_band": {pkg.KERNEL_NAMES[k]: b.opt.band(k)[0]
+                            for k in (pkg.K_MERGE, pkg.K_STEP_MERGE, pkg.K_STEP_SNAP_MERGE) if b.opt.band_state(k)[2]}}
     b.close()
-    return wall, ev_ms, kernels
+    return wall, ev_ms, kernels, tuning
 
 
 def repeats(cfg, n: int = 5, steps: int = 50, warmup: int = 10, gemm=False):
@@ -493,7 +516,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    wall, ev_ms, kernels = timed_region(cfg, args.steps, args.warmup, gemm=(cfg.name == "overlap"))
+    wall, ev_ms, kernels, tuning = timed_region(cfg, args.steps, args.warmup, gemm=(cfg.name == "overlap"))
     ms_per_step = wall / args.steps * 1e3
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     for name, k in kernels.items():
@@ -522,6 +545,7 @@ def main() -> int:
                         "GBps": round(k["GBps"], 1),
                         "frac_of_hbm_peak": round(k["frac_of_hbm_peak"], 4)} for n, k in kernels.items()},
     }
+    out["band_tuning"] = tuning
     step_bytes = sum(k["algorithmic_bytes"] * k["launches"] for k in kernels.values()) / args.steps
     out["whole_step"] = {"algorithmic_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                          "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}

@@ -186,7 +186,7 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
  *       pointers of the previous call (the table is re-uploaded only when it changes).
  * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
- * in the order given, one common row stride ld with P <= ld < P + 32 floats and ld a multiple of 4,
+ * in the order given, one common row stride ld with P <= ld < P + 256 floats and ld a multiple of 4,
  * base 16-byte aligned -- the kernels address them by arithmetic alone (fastest; fastest of all when
  * ld is a multiple of 32, so that rows are 128-byte aligned to each other).  The up to 31 floats
  * between two rows are then padding that BELONGS TO THE MATRIX: the library reads and overwrites
@@ -240,7 +240,7 @@ int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begi
 /* Layout of the library-owned buffers inside the workspace, for inspection by tests and tools:
  * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
  * *P_padded = elements per row: the row stride ld when x and v were bound as W x P matrices (rows
- * mirror that layout), otherwise every tensor padded to a multiple of 64 elements (plus 32).
+ * mirror that layout), otherwise every tensor padded to a multiple of 64 elements (plus 256).
  * ESTATE if not bound. */
 int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
 
@@ -258,6 +258,27 @@ int dasgd_profile(dasgd_ctx *ctx, int every_n, int max_records);
  * or last read: the summed duration of the timed launches, how many were timed, and how many were
  * launched in all; then reset the three.  Any output pointer may be NULL. */
 int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *timed, int64_t *launched);
+
+/* Work order of the matrix-layout kernels that read the average (folded local step, merge).  Their
+ * workgroups walk the W x P matrix in bands: 2^log_band column windows (1 KiB each, per L2 partition)
+ * of replica 0, the same windows of replica 1, ..., then the next band, so that a band's piece of the
+ * average is read from HBM once and from the L2 afterwards.  Which band length is fastest depends on P,
+ * W and on what runs around the kernel (measured on MI355X: up to 8 % between lengths, with a
+ * different winner for each benchmark shape), so by default the library measures it in place: the
+ * first 16 launches of such a kernel rotate through five lengths, three launches of each bracketed
+ * by timing events on main_stream; finished events are collected without waiting at later launches,
+ * and the fastest length is kept from then on.  The order never changes results: every element is
+ * computed by the same arithmetic whichever workgroup handles it (bit-identical, tested).
+ *   log_band  -1: measure (default);  0..11: use this length (clamped to the row length).
+ * May be called at any time.  EINVAL outside -1..11. */
+int dasgd_set_band(dasgd_ctx *ctx, int log_band);
+
+/* Band length in use for kernel `kernel` (DASGD_K_STEP_MERGE, DASGD_K_STEP_SNAP_MERGE or DASGD_K_MERGE):
+ * *log_band = the fixed or measured value, -1 while the measurement is still running; *settled = 1
+ * once it is final; *trials = timed trial launches issued so far for this kernel (0: it has not run
+ * more than once yet).  Looks at finished timing events but never waits.  Any output pointer may be
+ * NULL.  ESTATE if not bound. */
+int dasgd_band(dasgd_ctx *ctx, int kernel, int *log_band, int *settled, int *trials);
 
 /* HIP error code of the most recent DASGD_EHIP (0 if none). */
 int dasgd_last_hip_error(const dasgd_ctx *ctx);

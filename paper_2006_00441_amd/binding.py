@@ -56,6 +56,8 @@ EXPORTS = {
     "dasgd_pending_average": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, ctypes.POINTER(ctypes.c_size_t)]),
     "dasgd_profile": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
     "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64, _pi64]),
+    "dasgd_set_band": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "dasgd_band": (ctypes.c_int, [_vp, ctypes.c_int, _pint, _pint, _pint]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
 }
@@ -223,6 +225,26 @@ class DaSGD:
         self._check("dasgd_profile_read", self._lib.dasgd_profile_read(self._h, int(kernel), ctypes.byref(ms),
                                                                        ctypes.byref(n), ctypes.byref(m)))
         return float(ms.value), int(n.value), int(m.value)
+
+    def set_band(self, log_band: int) -> None:
+        """-1: measure the band length in place (default); 0..11: fix it."""
+        self._check("dasgd_set_band", self._lib.dasgd_set_band(self._h, int(log_band)))
+
+    def band(self, kernel: int) -> Tuple[int, bool]:
+        """(log2 of the band length in use for `kernel`, -1 while still being measured; settled?)"""
+        lb, st, _ = self.band_state(kernel)
+        return lb, st
+
+    def band_state(self, kernel: int) -> Tuple[int, bool, int]:
+        """(log2 band length or -1, settled?, timed trial launches issued so far)"""
+        lb = ctypes.c_int(); st = ctypes.c_int(); tr = ctypes.c_int()
+        self._check("dasgd_band", self._lib.dasgd_band(self._h, int(kernel), ctypes.byref(lb), ctypes.byref(st),
+                                                       ctypes.byref(tr)))
+        return int(lb.value), bool(st.value), int(tr.value)
+
+    def bands_in_flux(self) -> bool:
+        """True while a band measurement has started and not finished (never blocks)."""
+        return any(tr > 0 and not st for _, st, tr in (self.band_state(k) for k in (K_MERGE, K_STEP_MERGE, K_STEP_SNAP_MERGE)))
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

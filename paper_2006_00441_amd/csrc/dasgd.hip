@@ -32,6 +32,25 @@ struct ProfRec {
     hipEvent_t start, stop;
 };
 
+// Which band length (see decode_block) is fastest depends on the row length and on what runs around
+// the kernel, so it is measured where it matters: in the caller's own steps.  The first launches of
+// a kernel kind rotate through the candidates, a few of them bracketed by timing events; finished
+// events are collected with non-blocking queries at later launches (the host never waits), and once
+// every candidate has its samples the fastest is kept.  The band length only permutes which
+// workgroup handles which block: results are bit-identical for every choice.
+struct BandTuner {
+    static constexpr int kMaxCand = 5, kSamples = 3;
+    int cand[kMaxCand] = {0, 8, 9, 10, 11};     // log2 of the band length
+    int n_cand = 0;                             // 0: candidates not yet fitted to the row length
+    double sum_ms[kMaxCand] = {};
+    int done[kMaxCand] = {}, issued[kMaxCand] = {};
+    int64_t launches = 0;
+    int chosen = -1;                            // index into cand once decided
+    struct Rec { int cand; hipEvent_t start, stop; };
+    std::deque<Rec> inflight;
+    std::vector<hipEvent_t> spare;
+};
+
 struct Layout {                     // byte offsets into the workspace
     size_t chunks, xp, vp, gp[kGTables], S, A, total;
     int64_t P_pad, n_chunks;        // P_pad: elements per snapshot row / average
@@ -79,9 +98,11 @@ struct dasgd_ctx {
     int snap_slot = 0;
     // matrix layout: x, v (and g) are W x P row-major matrices with one row stride, 16-byte aligned
     bool xv_matrix = false, g_matrix = false;
-    int64_t ld = 0;                 // row stride of that matrix in elements (P <= ld < P + 32)
+    int64_t ld = 0;                 // row stride of that matrix in elements (P <= ld < P + 256)
     float *x0 = nullptr, *v0 = nullptr;
     const float *g0 = nullptr;
+    int band_fixed = -1;            // >= 0: log2 of the band length set by the caller; -1: measured (BandTuner)
+    BandTuner tuner[DASGD_K_COUNT];
     bool idx32 = false;             // 64 <= P/4 and W*P/4 + 64 < 2^31: the column-aware flat kernels apply
                                     // (32-bit indices; a 64-element block spans at most two rows)
     std::deque<Pending> pending;
@@ -122,7 +143,7 @@ bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 // mirror that layout, row stride included (so one flat index addresses x, v, g and the snapshot
 // alike).  The byte offsets of the padded layout are used in both cases: the workspace size must not
 // depend on pointers that dasgd_workspace_bytes never sees.
-constexpr int64_t kMaxRowPad = 32;  // a matrix row may be followed by fewer than this many padding floats
+constexpr int64_t kMaxRowPad = 256;  // a matrix row may be followed by fewer than this many padding floats
 
 Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false, int64_t ld = 0)
 {
@@ -224,6 +245,102 @@ int prof_close(dasgd_ctx *c, hipStream_t s, int rec_index)
 {
     if (rec_index < 0) return DASGD_OK;
     HIPCHK(c, hipEventRecord(c->prof_recs[rec_index].stop, s));
+    return DASGD_OK;
+}
+
+// Collect the trials that have finished (never waits).
+int band_poll(dasgd_ctx *c, BandTuner &t)
+{
+    while (!t.inflight.empty()) {
+        BandTuner::Rec &r = t.inflight.front();
+        const hipError_t q = hipEventQuery(r.stop);
+        if (q == hipErrorNotReady) {
+            (void)hipGetLastError();            // "not ready" is an answer, not a failure: do not leave it behind
+            break;
+        }
+        HIPCHK(c, q);
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, r.start, r.stop));
+        t.sum_ms[r.cand] += ms;
+        t.done[r.cand] += 1;
+        t.spare.push_back(r.start);
+        t.spare.push_back(r.stop);
+        t.inflight.pop_front();
+    }
+    return DASGD_OK;
+}
+
+// Collect, and keep the fastest candidate once every one has its samples.
+int band_decide(dasgd_ctx *c, BandTuner &t)
+{
+    const int rc = band_poll(c, t);
+    if (rc != DASGD_OK) return rc;
+    for (int i = 0; i < t.n_cand; ++i)
+        if (t.done[i] < BandTuner::kSamples) return DASGD_OK;
+    int best = 0;
+    for (int i = 1; i < t.n_cand; ++i)
+        if (t.sum_ms[i] / t.done[i] < t.sum_ms[best] / t.done[best]) best = i;
+    t.chosen = best;
+    for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
+    t.spare.clear();
+    return DASGD_OK;
+}
+
+// Band length for the next launch of kernel kind `kid` over rows of row4 128-bit columns.  *trial >= 0:
+// the launch is a timed trial, band_close must follow it.
+int band_pick(dasgd_ctx *c, int kid, unsigned row4, unsigned *log_band, int *trial)
+{
+    *trial = -1;
+    if (c->band_fixed >= 0) {
+        *log_band = decode_clamp_log_band(row4, (unsigned)c->band_fixed);
+        return DASGD_OK;
+    }
+    BandTuner &t = c->tuner[kid];
+    if (t.n_cand == 0) {                        // fit the candidates to the row length, drop duplicates
+        int n = 0;
+        for (int i = 0; i < BandTuner::kMaxCand; ++i) {
+            const int lb = (int)decode_clamp_log_band(row4, (unsigned)t.cand[i]);
+            bool dup = false;
+            for (int k = 0; k < n; ++k) dup = dup || t.cand[k] == lb;
+            if (!dup) t.cand[n++] = lb;
+        }
+        t.n_cand = n;
+        if (n == 1) t.chosen = 0;
+    }
+    if (t.chosen < 0) {
+        const int rc = band_decide(c, t);
+        if (rc != DASGD_OK) return rc;
+    }
+    if (t.chosen >= 0) {
+        *log_band = (unsigned)t.cand[t.chosen];
+        return DASGD_OK;
+    }
+    const int64_t n = t.launches++;
+    int pick = -1;
+    if (n > 0)                                  // (the first launch of a kind runs cold: not timed)
+        for (int i = 0; i < t.n_cand; ++i)
+            if (t.issued[i] < BandTuner::kSamples && (pick < 0 || t.issued[i] < t.issued[pick])) pick = i;
+    if (pick < 0) {                             // cold launch, or all trials issued and results still to come
+        *log_band = (unsigned)t.cand[0];
+        return DASGD_OK;
+    }
+    BandTuner::Rec r;
+    r.cand = pick;
+    for (hipEvent_t *e : {&r.start, &r.stop}) {
+        if (!t.spare.empty()) { *e = t.spare.back(); t.spare.pop_back(); }
+        else HIPCHK(c, hipEventCreate(e));
+    }
+    HIPCHK(c, hipEventRecord(r.start, c->main_s));
+    t.inflight.push_back(r);
+    t.issued[pick] += 1;
+    *log_band = (unsigned)t.cand[pick];
+    *trial = pick;
+    return DASGD_OK;
+}
+int band_close(dasgd_ctx *c, int kid, int trial)
+{
+    if (trial < 0) return DASGD_OK;
+    HIPCHK(c, hipEventRecord(c->tuner[kid].inflight.back().stop, c->main_s));
     return DASGD_OK;
 }
 
@@ -380,7 +497,7 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     c->ld = matrix ? ldx : 0;
     c->x0 = x[0];
     c->v0 = v[0];
-    c->idx32 = matrix && c->ld / 4 >= 64 && (int64_t)c->W * c->ld / 4 + 64 < (1ll << 31) && (int64_t)decode_grid((unsigned)c->W, (unsigned)(c->ld / 4)) < (1ll << 31);
+    c->idx32 = matrix && c->ld / 4 >= 64 && (int64_t)c->W * c->ld / 4 + 64 < (1ll << 31) && decode_grid((unsigned)c->W, (unsigned)(c->ld / 4), 11) < (1ull << 31);
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
@@ -522,7 +639,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                       : fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
-        int rec;
+        int rec, trial = -1;
         int rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         const bool flat = c->xv_matrix && c->g_matrix && (!fold || c->idx32);
@@ -557,10 +674,13 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             if (fold) {
                 const v4f *A4 = reinterpret_cast<const v4f *>(A);
                 const unsigned row4 = (unsigned)(c->ld / 4);
-                const dim3 fgrid(decode_grid((unsigned)c->W, row4));
+                unsigned lb;
+                rc = band_pick(c, kid, row4, &lb, &trial);
+                if (rc != DASGD_OK) return rc;
+                const dim3 fgrid((unsigned)decode_grid((unsigned)c->W, row4, lb));
 #define DASGD_LAUNCH_FOLD(SNAP, WT)                                                                             \
     hipLaunchKernelGGL((k_step_merge_flat<SNAP, WT>), fgrid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4,     \
-                       (unsigned)n4, row4, c->W, c->lr, c->momentum, c->wd, om)
+                       (unsigned)n4, row4, c->W, lb, c->lr, c->momentum, c->wd, om)
 #define DASGD_LAUNCH_FOLD_W(SNAP)                                                                               \
     switch (c->W) {                                                                                             \
     case 1:  DASGD_LAUNCH_FOLD(SNAP, 1);  break;                                                                \
@@ -596,6 +716,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
 #undef DASGD_LAUNCH_TABLE
         }
         HIPCHK(c, hipGetLastError());
+        rc = band_close(c, kid, trial);
+        if (rc != DASGD_OK) return rc;
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
     }
@@ -648,7 +770,7 @@ int dasgd_merge(dasgd_ctx *c)
         if (side_stream_mean(c) && !c->pending.front().awaited) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
         const float *Y = c->y_in_snap ? snap_ptr(c, c->snap_slot) : nullptr;
         const float om = 1.0f - c->xi;
-        int rec;
+        int rec, trial = -1;
         int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         if (c->xv_matrix && c->idx32) {
@@ -657,14 +779,17 @@ int dasgd_merge(dasgd_ctx *c)
             const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
             const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
             const unsigned n4 = (unsigned)(row4 * c->W);
-            const dim3 grid(decode_grid((unsigned)c->W, (unsigned)row4));
+            unsigned lb;
+            rc = band_pick(c, DASGD_K_MERGE, (unsigned)row4, &lb, &trial);
+            if (rc != DASGD_OK) return rc;
+            const dim3 grid((unsigned)decode_grid((unsigned)c->W, (unsigned)row4, lb));
             switch (c->W) {
-            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
-            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
-            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
-            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
-            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
-            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, om); break;
+            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
+            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
+            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
+            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
+            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
+            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
             }
         } else {
             const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
@@ -676,6 +801,8 @@ int dasgd_merge(dasgd_ctx *c)
                 hipLaunchKernelGGL((k_merge<false>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
         }
         HIPCHK(c, hipGetLastError());
+        rc = band_close(c, DASGD_K_MERGE, trial);
+        if (rc != DASGD_OK) return rc;
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
     }
@@ -801,6 +928,31 @@ int dasgd_profile_read(dasgd_ctx *c, int kernel, double *total_ms, int64_t *time
     return DASGD_OK;
 }
 
+int dasgd_set_band(dasgd_ctx *c, int log_band)
+{
+    if (!c || log_band < -1 || log_band > 11) return DASGD_EINVAL;
+    c->band_fixed = log_band;
+    return DASGD_OK;
+}
+
+int dasgd_band(dasgd_ctx *c, int kernel, int *log_band, int *settled, int *trials)
+{
+    if (!c || kernel < 0 || kernel >= DASGD_K_COUNT) return DASGD_EINVAL;
+    if (!c->bound || c->dry) return DASGD_ESTATE;
+    BandTuner &t = c->tuner[kernel];
+    if (c->band_fixed < 0 && t.n_cand > 0 && t.chosen < 0) {     // a decision may be due: look, without waiting
+        const int rc = band_decide(c, t);
+        if (rc != DASGD_OK) return rc;
+    }
+    if (log_band) *log_band = c->band_fixed >= 0 ? c->band_fixed : t.chosen >= 0 ? t.cand[t.chosen] : -1;
+    if (settled) *settled = (c->band_fixed >= 0 || t.chosen >= 0) ? 1 : 0;
+    if (trials) {
+        *trials = 0;
+        for (int i = 0; i < t.n_cand; ++i) *trials += t.issued[i];
+    }
+    return DASGD_OK;
+}
+
 int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
 
 void dasgd_destroy(dasgd_ctx *c)
@@ -817,6 +969,10 @@ void dasgd_destroy(dasgd_ctx *c)
         for (int b = 0; b < kGTables; ++b) if (c->g_ev[b]) (void)hipEventDestroy(c->g_ev[b]);
         for (const ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
         for (const ProfRec &r : c->prof_pool) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (BandTuner &t : c->tuner) {
+            for (const BandTuner::Rec &r : t.inflight) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+            for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
+        }
         if (c->g_pinned) (void)hipHostFree(c->g_pinned);
     }
     delete c;

@@ -191,32 +191,52 @@ k_local_step_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restric
 // Work decomposition of the matrix-layout kernels that need the column of an element (to read the
 // average A): the flat index space [0, W*row4) of 128-bit elements is cut into aligned blocks of 64
 // (one wavefront, one whole kilobyte per array whatever the row length -- misaligned kilobytes cost
-// 15 % of the bandwidth on MI355X).  Blocks are issued grouped by column window, the W replicas of a
-// window back to back on ONE XCD (workgroups are dealt round-robin to the 8 XCDs, each with its own
-// L2): the window of A is fetched from HBM once and re-read from that L2 by the other W-1 replicas.
-// A block that holds the boundary between rows j and j+1 belongs to row j and serves both.
+// 15 % of the bandwidth on MI355X).  A block that holds the boundary between rows j and j+1 belongs
+// to row j and serves both.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2;
+// the blocks of an XCD are issued in bands: B = 2^log_band column windows of row 0, the same windows
+// of row 1, ... of row W-1, then the next band.  The band's piece of A (B KiB per XCD) is fetched from
+// HBM once and re-read from that L2 by the other W-1 rows.  B = 1 issues the W replicas of one
+// window back to back; which B is fastest depends on the row length (the host measures it).
 // Returns false if this workgroup/lane has nothing to do; else the flat index i and the column c.
-__device__ __forceinline__ bool decode_block(unsigned b, unsigned W, unsigned row4, unsigned n4,
-                                             unsigned &i, unsigned &c)
+// The part of it that does not depend on the lane (also callable on the host, where the tests check
+// that every block of every row is owned exactly once): block index, and the flat range of its row.
+__host__ __device__ __forceinline__ bool decode_owner(unsigned b, unsigned W, unsigned row4, unsigned log_band,
+                                                      unsigned &blk, unsigned &lo, unsigned &hi)
 {
     const unsigned xcd = b & 7u, slot = b >> 3;
-    const unsigned j = slot % W;
-    const unsigned q = (slot / W) * 8u + xcd;                // column window
-    const unsigned lo = j * row4, hi = lo + row4;            // flat range of row j
-    const unsigned first = j ? (lo >> 6) + 1u : 0u;          // first block owned by row j
-    const unsigned last = (j == W - 1u) ? ((n4 - 1u) >> 6) : (hi >> 6);
-    const unsigned blk = first + q;
-    if (blk > last) return false;
+    const unsigned w = slot & ((1u << log_band) - 1u), t = slot >> log_band;
+    const unsigned j = t % W, band = t / W;
+    const unsigned q = (((band << log_band) + w) << 3) + xcd;    // column window
+    lo = j * row4; hi = lo + row4;                           // flat range of row j
+    const unsigned first = (lo + 63u) >> 6;                  // first block owned by row j
+    const unsigned last = (hi - 1u) >> 6;                    // last one (it may reach into row j+1)
+    blk = first + q;
+    return blk <= last;
+}
+__device__ __forceinline__ bool decode_block(unsigned b, unsigned W, unsigned row4, unsigned n4, unsigned log_band,
+                                             unsigned &i, unsigned &c)
+{
+    unsigned blk, lo, hi;
+    if (!decode_owner(b, W, row4, log_band, blk, lo, hi)) return false;
     i = blk * kWave + threadIdx.x;
     if (i >= n4) return false;
     c = (i >= hi) ? i - hi : i - lo;
     return true;
 }
-// Number of workgroups decode_block needs.
-static inline unsigned decode_grid(unsigned W, unsigned row4)
+// Largest useful log_band for a row length, and the number of workgroups decode_block needs.
+static inline unsigned decode_windows_per_xcd(unsigned row4)
 {
-    const unsigned windows = (row4 >> 6) + 2u;               // blocks one row can own, upper bound
-    return (windows + 7u) / 8u * 8u * W;
+    return ((row4 >> 6) + 2u + 7u) / 8u;                     // blocks one row can own (upper bound), per XCD
+}
+static inline unsigned decode_clamp_log_band(unsigned row4, unsigned log_band)
+{
+    while (log_band > 0 && (1u << log_band) > decode_windows_per_xcd(row4)) --log_band;
+    return log_band;
+}
+static inline uint64_t decode_grid(unsigned W, unsigned row4, unsigned log_band)
+{
+    const uint64_t per_xcd = decode_windows_per_xcd(row4), B = 1ull << log_band;
+    return (per_xcd + B - 1) / B * B * 8ull * W;
 }
 
 // Matrix layout, local step with this step's merge folded in (paper Eq. 2, both branches in one
@@ -227,11 +247,11 @@ static inline unsigned decode_grid(unsigned W, unsigned row4)
 template <bool SNAP, int WT>   // WT > 0: W known at compile time; 0: any W
 __global__ void __launch_bounds__(kWave)
 k_step_merge_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
-                  const v4f *__restrict__ A, unsigned n4, unsigned row4, int W,
+                  const v4f *__restrict__ A, unsigned n4, unsigned row4, int W, unsigned log_band,
                   float lr, float momentum, float wd, float om)
 {
     unsigned i, c;
-    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, i, c)) return;
+    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, log_band, i, c)) return;
     v4f xr = ld4<true>(x + i);
     v4f vr = ld4<true>(v + i);
     const v4f gr = ld4<true>(g + i);
@@ -508,10 +528,10 @@ k_merge(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, const f
 template <int WT>   // WT > 0: W known at compile time; 0: any W
 __global__ void __launch_bounds__(kWave)
 k_merge_flat(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
-             unsigned n4, unsigned row4, int W, float om)
+             unsigned n4, unsigned row4, int W, unsigned log_band, float om)
 {
     unsigned i, c;
-    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, i, c)) return;
+    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, log_band, i, c)) return;
     const v4f a = ld4<false>(A + c);
     const v4f y = ld4<true>(Y + i);
     st4<true>(X + i, merge4(y, a, om));

@@ -63,6 +63,14 @@ def test_create_validates_arguments():
         with pytest.raises(DasgdError):
             o.set_snapshot(m)
     o.set_snapshot(pkg.SNAPSHOT_COPY); o.set_snapshot(pkg.SNAPSHOT_ZERO_COPY)
+    for b in (-2, 12):
+        with pytest.raises(DasgdError):
+            o.set_band(b)
+    for b in (-1, 0, 11):
+        o.set_band(b)
+    with pytest.raises(DasgdError) as e:
+        o.band(pkg.K_STEP_MERGE)                 # nothing bound yet
+    assert e.value.code == pkg.DASGD_ESTATE
     o.destroy()
 
 
@@ -71,7 +79,7 @@ def test_workspace_bytes_and_shapes():
     assert o.workspace_bytes([64, 1000, 5001]) == 0          # does not sum to P
     assert o.workspace_bytes([64, 0, 6000]) == 0
     n = o.workspace_bytes([64, 1000, 5000])
-    ppad = 64 + 1024 + 5056 + 32         # tensors padded to 64 elements, plus room for matrix row padding
+    ppad = 64 + 1024 + 5056 + 256        # tensors padded to 64 elements, plus room for matrix row padding
     slots = 3
     assert n >= 4 * slots * (8 + 1) * ppad and n % 256 == 0
     with pytest.raises(DasgdError) as e:
