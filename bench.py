@@ -128,10 +128,19 @@ class Bench:
             self.step()
             extra += 1
         self.torch.cuda.synchronize()
-        while self.opt.bands_in_flux() and extra < limit:
-            for _ in range(self.cfg.tau):
+        prev = None
+        while extra < limit:
+            # (trial launches issued, settled) per kernel kind; a kind that is neither settled nor issuing
+            # trials any more is simply not launched in this configuration: nothing to wait for
+            now = {k: self.opt.band_state(k)[1:] for k in self.pkg.KERNEL_NAMES}
+            busy = [k for k, (settled, trials) in now.items()
+                    if trials > 0 and not settled and (prev is None or prev[k][1] != trials)]
+            if not busy:
+                break
+            prev = now
+            for _ in range(2 * self.cfg.tau):
                 self.step()
-            extra += self.cfg.tau
+            extra += 2 * self.cfg.tau
             self.torch.cuda.synchronize()
         return extra
 
@@ -207,8 +216,7 @@ def timed_region(cfg, steps: int, warmup: int, gemm: bool = False):
             kernels[name] = {"launches": launched, "timed_launches": n, "avg_ms": ms / n}
     b.opt.profile(0)
     tuning = {"extra_untimed_steps": tuning_steps,
-              "log2_band": {pkg.KERNEL_NAMES[k]: b.opt.band(k)[0]
-                            for k in (pkg.K_MERGE, pkg.K_STEP_MERGE, pkg.K_STEP_SNAP_MERGE) if b.opt.band_state(k)[2]}}
+              "log2_band": {name: b.opt.band(k)[0] for k, name in pkg.KERNEL_NAMES.items() if b.opt.band_state(k)[2]}}
     b.close()
     return wall, ev_ms, kernels, tuning
 

@@ -244,7 +244,7 @@ class DaSGD:
 
     def bands_in_flux(self) -> bool:
         """True while a band measurement has started and not finished (never blocks)."""
-        return any(tr > 0 and not st for _, st, tr in (self.band_state(k) for k in (K_MERGE, K_STEP_MERGE, K_STEP_SNAP_MERGE)))
+        return any(tr > 0 and not st for _, st, tr in (self.band_state(k) for k in KERNEL_NAMES))
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

@@ -494,9 +494,12 @@ def pkg_kernel_names():
 # ------------------------------------------------------------------------------------------------
 # band order of the column-aware kernels: any band length, and the in-place measurement, give the same bits
 @pytest.mark.parametrize("fusion,snapshot", [(2, 1), (2, 0), (0, 0), (1, 0)])
+@pytest.mark.parametrize("tau,d", [(1, 2), (3, 1)])
 @pytest.mark.parametrize("W,numel", [(8, [64 * 4 * 37 + 12, 1000, 36]), (3, [4096 * 5]), (5, [260])])
-def test_band_length_never_changes_results(W, numel, fusion, snapshot):
-    cfg = small(tau=1, d=2, W=W, steps=24, params=custom_param_set(numel))
+def test_band_length_never_changes_results(W, numel, fusion, snapshot, tau, d):
+    """Fixed band lengths, and the measuring mode (-1), which rotates through band lengths while it
+    measures."""
+    cfg = small(tau=tau, d=d, W=W, steps=24, params=custom_param_set(numel))
     outs = {}
     for band in (-1, 0, 1, 3, 8, 11):
         run = GpuRun(cfg, fusion=fusion, snapshot=snapshot)
