@@ -280,6 +280,15 @@ int dasgd_set_band(dasgd_ctx *ctx, int log_band);
  * NULL.  ESTATE if not bound. */
 int dasgd_band(dasgd_ctx *ctx, int kernel, int *log_band, int *settled, int *trials);
 
+/* Host-only self-check of the index arithmetic behind that work order, with the very function the
+ * kernels use: for a W x (4*row4)-float matrix and band length 2^log_band (clamped as the library
+ * would), every aligned 64-column block of the flat index space must be handled by exactly one
+ * workgroup, on behalf of the row that holds its first element, and no workgroup may point past the
+ * end.  Returns 0 if so, 1..4 naming the violated property (start past the end, wrong row, handled
+ * twice, never handled); EINVAL for sizes outside what those kernels accept (row4 < 64, W*row4 + 64
+ * >= 2^31, log_band outside 0..11). */
+int dasgd_check_block_map(int W, int64_t row4, int log_band);
+
 /* HIP error code of the most recent DASGD_EHIP (0 if none). */
 int dasgd_last_hip_error(const dasgd_ctx *ctx);
 

@@ -58,6 +58,7 @@ EXPORTS = {
     "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64, _pi64]),
     "dasgd_set_band": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_band": (ctypes.c_int, [_vp, ctypes.c_int, _pint, _pint, _pint]),
+    "dasgd_check_block_map": (ctypes.c_int, [ctypes.c_int, _i64, ctypes.c_int]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
 }
@@ -106,6 +107,15 @@ def choose_delay(t_c: float, t_p: float) -> Tuple[int, int]:
     if rc < 0:
         raise DasgdError("dasgd_choose_delay", rc)
     return int(d.value), int(tau.value)
+
+
+def check_block_map(W: int, row4: int, log_band: int) -> int:
+    """0 if the work order of the column-aware kernels covers a W x 4*row4 matrix exactly once
+    (dasgd_check_block_map); 1..4 name the violated property; raises on sizes the kernels do not take."""
+    rc = lib().dasgd_check_block_map(int(W), int(row4), int(log_band))
+    if rc < 0:
+        raise DasgdError("dasgd_check_block_map", rc)
+    return rc
 
 
 def _ptr_array(ptrs: Sequence[int]):

@@ -953,6 +953,28 @@ int dasgd_band(dasgd_ctx *c, int kernel, int *log_band, int *settled, int *trial
     return DASGD_OK;
 }
 
+int dasgd_check_block_map(int W, int64_t row4, int log_band)
+{
+    if (W < 1 || W > 65535 || row4 < 64 || log_band < 0 || log_band > 11) return DASGD_EINVAL;
+    if ((int64_t)W * row4 + 64 >= (1ll << 31)) return DASGD_EINVAL;
+    const unsigned w = (unsigned)W, r4 = (unsigned)row4, n4 = w * r4;
+    const unsigned lb = decode_clamp_log_band(r4, (unsigned)log_band);
+    const uint64_t grid = decode_grid(w, r4, lb);
+    if (grid >= (1ull << 31)) return DASGD_EINVAL;
+    const unsigned n_blocks = (n4 + 63u) / 64u;
+    std::vector<unsigned char> seen(n_blocks, 0);
+    for (uint64_t b = 0; b < grid; ++b) {
+        unsigned blk, lo, hi;
+        if (!decode_owner((unsigned)b, w, r4, lb, blk, lo, hi)) continue;
+        if (blk >= n_blocks) return 1;                                  // a workgroup would start past the end
+        if (lo / r4 != (unsigned)(((uint64_t)blk * 64u) / r4)) return 2;   // owned by a row that does not hold its first element
+        if (seen[blk]++) return 3;                                      // handled twice
+    }
+    for (unsigned k = 0; k < n_blocks; ++k)
+        if (!seen[k]) return 4;                                         // never handled
+    return DASGD_OK;
+}
+
 int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
 
 void dasgd_destroy(dasgd_ctx *c)

@@ -194,3 +194,17 @@ def test_step_is_the_canonical_loop():
             assert (began, merged) == (bd, md)
             assert a.query() == b.query()
         a.destroy(); b.destroy()
+
+
+def test_block_map_of_the_column_aware_kernels_covers_every_block_once():
+    """The index arithmetic that decides which workgroup touches which kilobyte, checked on the host
+    with the function the kernels themselves call: ragged and aligned rows, tiny and huge, every band
+    length.  A gap would leave elements un-updated; an overlap or an overrun would race or fault."""
+    shapes = [(W, r) for W in (1, 2, 3, 5, 8, 16, 17) for r in (64, 65, 100, 127, 128, 129, 640, 1000, 4099)]
+    shapes += [(8, 6389258), (8, 6389312), (16, 6389258), (4, 83785472), (8, 2**28 - 16), (3, 700000001), (64, 33554000)]
+    for W, row4 in shapes:
+        for lb in ((0, 1, 3, 8, 9, 10, 11) if row4 < 10**6 else (0, 9, 11)):
+            assert pkg.check_block_map(W, row4, lb) == 0, (W, row4, lb)
+    for bad in ((0, 64, 0), (8, 63, 0), (8, 2**28, 0), (8, 1000, 12), (8, 1000, -1)):
+        with pytest.raises(DasgdError):
+            pkg.check_block_map(*bad)
