@@ -270,7 +270,9 @@ int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *ti
  * and the fastest length is kept from then on.  The order never changes results: every element is
  * computed by the same arithmetic whichever workgroup handles it (bit-identical, tested).
  *   log_band  -1: measure (default);  0..11: use this length (clamped to the row length).
- * May be called at any time.  EINVAL outside -1..11. */
+ * May be called at any time.  EINVAL outside -1..11.  A caller that captures the step calls into a HIP
+ * graph fixes the length first (the measurement queries events, which a capturing stream forbids) --
+ * for instance to the value dasgd_band reported after a few eager steps. */
 int dasgd_set_band(dasgd_ctx *ctx, int log_band);
 
 /* Band length in use for kernel `kernel` (DASGD_K_STEP_MERGE, DASGD_K_STEP_SNAP_MERGE or DASGD_K_MERGE):
