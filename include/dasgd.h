@@ -134,6 +134,13 @@ int dasgd_set_lr(dasgd_ctx *ctx, float lr);
 /* Choose the schedule (DASGD_SCHED_*).  Only legal while no average is pending. */
 int dasgd_set_schedule(dasgd_ctx *ctx, int schedule);
 
+/* In the overlap schedules a mean that reads and writes fewer than `bytes` bytes ((W+1) rows of fp32)
+ * is launched on main_stream after all: handing work to the side stream and back costs two
+ * cross-stream waits of 6-10 us each on MI355X, more than so small a mean takes (at 6 TB/s, 64 MiB are
+ * 11 us).  Default 64 MiB; 0 sends every mean to the side stream.  Results do not depend on it.
+ * ESTATE while averages are pending or an average is due. */
+int dasgd_set_side_stream_threshold(dasgd_ctx *ctx, size_t bytes);
+
 /* Choose the fusion level (DASGD_FUSE_*).  Only legal while no average is pending. */
 int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
 

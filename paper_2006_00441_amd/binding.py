@@ -40,6 +40,7 @@ EXPORTS = {
     "dasgd_set_xi": (ctypes.c_int, [_vp, ctypes.c_float]),
     "dasgd_set_lr": (ctypes.c_int, [_vp, ctypes.c_float]),
     "dasgd_set_schedule": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "dasgd_set_side_stream_threshold": (ctypes.c_int, [_vp, ctypes.c_size_t]),
     "dasgd_set_fusion": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_set_snapshot": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_workspace_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int, _pi64]),
@@ -235,6 +236,10 @@ class DaSGD:
         self._check("dasgd_profile_read", self._lib.dasgd_profile_read(self._h, int(kernel), ctypes.byref(ms),
                                                                        ctypes.byref(n), ctypes.byref(m)))
         return float(ms.value), int(n.value), int(m.value)
+
+    def set_side_stream_threshold(self, nbytes: int) -> None:
+        """Means smaller than this stay on the main stream even in the overlap schedules (0: none do)."""
+        self._check("dasgd_set_side_stream_threshold", self._lib.dasgd_set_side_stream_threshold(self._h, int(nbytes)))
 
     def set_band(self, log_band: int) -> None:
         """-1: measure the band length in place (default); 0..11: fix it."""

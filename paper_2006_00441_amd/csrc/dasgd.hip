@@ -69,6 +69,7 @@ struct dasgd_ctx {
     int fusion = DASGD_FUSE_STEP_MERGE;
     int snapshot = DASGD_SNAPSHOT_ZERO_COPY;
     int slots = 1;
+    size_t side_min_bytes = (size_t)64 << 20;   // means that move less than this run on the main stream
     // binding
     bool bound = false, dry = false;
     int n_tensors = 0;
@@ -207,9 +208,14 @@ inline float *avg_ptr(const dasgd_ctx *c, int slot)
     return reinterpret_cast<float *>(c->ws + c->lay.A) + (size_t)slot * (size_t)c->lay.P_pad;
 }
 
+// The mean goes to the side stream in the overlap schedules -- unless it is so small that the two
+// cross-stream hand-overs (main -> side before it, side -> main after it; 6-10 us each on MI355X)
+// cost more than running it in line could ever lose.
 inline bool side_stream_mean(const dasgd_ctx *c)
 {
-    return c->schedule == DASGD_SCHED_OVERLAP || c->schedule == DASGD_SCHED_OVERLAP_FREE;
+    if (c->schedule != DASGD_SCHED_OVERLAP && c->schedule != DASGD_SCHED_OVERLAP_FREE) return false;
+    const size_t mean_bytes = sizeof(float) * (size_t)(c->W + 1) * (size_t)c->lay.P_pad;
+    return mean_bytes >= c->side_min_bytes;
 }
 
 inline bool begin_due(const dasgd_ctx *c)
@@ -414,6 +420,14 @@ int dasgd_set_schedule(dasgd_ctx *c, int schedule)
     if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_OVERLAP_FREE) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->schedule = schedule;
+    return DASGD_OK;
+}
+
+int dasgd_set_side_stream_threshold(dasgd_ctx *c, size_t bytes)
+{
+    if (!c) return DASGD_EINVAL;
+    if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
+    c->side_min_bytes = bytes;
     return DASGD_OK;
 }
 

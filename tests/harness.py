@@ -31,7 +31,10 @@ class GpuRun:
 
     def __init__(self, cfg: Config, layout: str = "arena", schedule: Optional[int] = None,
                  device: str = "cuda:0", xi: Optional[float] = None, fusion: Optional[int] = None,
-                 snapshot: Optional[int] = None):
+                 snapshot: Optional[int] = None, side_threshold: Optional[int] = 0):
+        """side_threshold: bytes below which the library keeps the mean on the main stream; 0 (the
+        default HERE, not the library's) sends every mean to the side stream so that small test
+        problems exercise the two-stream path; None leaves the library's default."""
         import paper_2006_00441_amd as pkg
         self.pkg = pkg
         self.cfg = cfg
@@ -64,6 +67,8 @@ class GpuRun:
         self.main.synchronize()
         self.opt = pkg.DaSGD(W, P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, xi=cfg.xi if xi is None else xi)
         self.ws = self.opt.bind_tensors(self.x, self.v, self.main, self.side)
+        if side_threshold is not None:
+            self.opt.set_side_stream_threshold(side_threshold)
         if schedule is not None:
             self.opt.set_schedule(schedule)
         if fusion is not None:

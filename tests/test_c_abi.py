@@ -63,6 +63,7 @@ def test_create_validates_arguments():
         with pytest.raises(DasgdError):
             o.set_snapshot(m)
     o.set_snapshot(pkg.SNAPSHOT_COPY); o.set_snapshot(pkg.SNAPSHOT_ZERO_COPY)
+    o.set_side_stream_threshold(0); o.set_side_stream_threshold(1 << 40)
     for b in (-2, 12):
         with pytest.raises(DasgdError):
             o.set_band(b)
