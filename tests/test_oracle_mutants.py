@@ -42,6 +42,16 @@ MUTANTS = {
                         "A[i] = NAME(pairwise_sum)(y, P, i, 0, W > 1 ? W - 1 : W) * inv;"),
     "mean_transposed_index": ("if (hi - lo == 1) return y[(int64_t)lo * P + i];",
                               "if (hi - lo == 1) return y[(int64_t)lo + i * 0 + (i % P)];"),
+    "merge_one_step_late": ("launch_step == k - o->d) {", "launch_step == k - o->d - 1) {"),
+    "merge_newest_not_oldest": ("NAME(dasgd_oracle_merge)(o->W, o->P, o->xi, o->x, o->fifo[o->head].A);",
+                                "NAME(dasgd_oracle_merge)(o->W, o->P, o->xi, o->x, "
+                                "o->fifo[(o->head + o->count - 1) % o->cap].A);"),
+    "merge_is_convex_in_xi_only": ("REAL om = (REAL)1 - xi;\n    #pragma omp parallel for schedule(static)\n"
+                                   "    for (int64_t i = 0; i < P; ++i)\n        for (int j = 0; j < W; ++j) {",
+                                   "REAL om = (REAL)1;\n    #pragma omp parallel for schedule(static)\n"
+                                   "    for (int64_t i = 0; i < P; ++i)\n        for (int j = 0; j < W; ++j) {"),
+    "mean_of_first_replica_only": ("A[i] = NAME(pairwise_sum)(y, P, i, 0, W) * inv;",
+                                   "A[i] = y[i] + (NAME(pairwise_sum)(y, P, i, 0, W) * inv) * (REAL)0;"),
     "average_after_merge": _swap_launch_and_merge,
     "momentum_reset_at_merge": ("        o->head = (o->head + 1) % o->cap;",
                                 "        memset(o->v, 0, sizeof(REAL) * (size_t)o->W * (size_t)o->P);\n"
