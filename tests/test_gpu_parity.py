@@ -537,3 +537,33 @@ def test_band_measurement_settles_without_blocking():
     run.close()
     ref = run_oracle(cfg.scaled(steps=cfg.steps + 1), "f64")
     assert max_scaled_error(cfg, x, ref) <= TOL
+
+
+# ------------------------------------------------------------------------------------------------
+# stream ordering under real concurrency: full-size kernels, the mean free to run beside everything
+@pytest.mark.parametrize("schedule_name", ["SCHED_OVERLAP", "SCHED_OVERLAP_FREE"])
+def test_full_size_overlap_with_foreign_work_equals_serial(schedule_name):
+    """At full size the kernels are long enough to expose a missing event edge: with a GEMM of the
+    caller's on the main stream before every step (the forward/backward stand-in of the overlap
+    workload) and the mean on the side stream, every replica must end with exactly the bits of the
+    single-stream schedule."""
+    import paper_2006_00441_amd as pkg
+    cfg = wl.get_config("overlap").scaled(steps=14)
+    idx = sample_indices(cfg)
+    outs = {}
+    for name in (schedule_name, "SCHED_SERIAL"):
+        snap = pkg.SNAPSHOT_COPY if schedule_name == "SCHED_OVERLAP_FREE" else pkg.SNAPSHOT_ZERO_COPY
+        run = GpuRun(cfg, schedule=getattr(pkg, name), snapshot=snap)
+        with torch.cuda.stream(run.main):
+            a = torch.randn(4096, 4096, device=run.dev, dtype=torch.bfloat16)
+            c = torch.empty_like(a)
+        for _ in range(cfg.steps):
+            with torch.cuda.stream(run.main):
+                torch.matmul(a, a, out=c)
+            run.step()
+        outs[name] = torch.from_numpy(run.weights(idx))
+        run.close()
+        del run
+    assert torch.equal(outs[schedule_name], outs["SCHED_SERIAL"])
+    ref = run_oracle(cfg, "f64", idx=idx)
+    assert max_scaled_error(cfg, outs["SCHED_SERIAL"].numpy(), ref, idx) <= TOL
