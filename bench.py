@@ -491,6 +491,9 @@ def main() -> int:
     ap.add_argument("--layout", default="matrix", choices=["matrix", "separate"],
                     help="matrix: x, v, g as W x P arenas (default); separate: one allocation per tensor")
     ap.add_argument("--fusion", type=int, default=None, help="fusion level 0..3 (default: the library's)")
+    ap.add_argument("--stand-in", default=None, choices=["none", "gemm", "alu"],
+                    help="forward/backward stand-in on the main stream before every step of the timed region: "
+                         "bf16 8192^3 GEMM (default for --workload overlap), the register-light ALU kernel, or none")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark: xi / d / tau study on the quadratic, one JSON line")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -524,7 +527,9 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    wall, ev_ms, kernels, tuning = timed_region(cfg, args.steps, args.warmup, gemm=(cfg.name == "overlap"))
+    stand_in = args.stand_in or ("gemm" if cfg.name == "overlap" else "none")
+    wall, ev_ms, kernels, tuning = timed_region(cfg, args.steps, args.warmup,
+                                                gemm={"none": False, "gemm": True, "alu": "alu"}[stand_in])
     ms_per_step = wall / args.steps * 1e3
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     for name, k in kernels.items():
@@ -544,7 +549,8 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.params.name}-shaped, {cfg.params.n_tensors} fp32 tensors, "
                                f"P={cfg.P}, W={cfg.W}, tau={cfg.tau}, d={cfg.d}, xi={cfg.xi}",
-                   "schedule": "overlap (mean on side stream)", "layout": args.layout, "replica_params": rp},
+                   "schedule": "overlap (mean on side stream)", "layout": args.layout, "replica_params": rp,
+                   "stand_in": stand_in},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac_of_hbm_peak"], "avg_ms": d["avg_ms"], "launches": d["launches"], "timed_launches": d["timed_launches"],
                      "algorithmic_bytes_per_launch": d["algorithmic_bytes"],
@@ -570,7 +576,7 @@ def main() -> int:
         if cfg.kind == "external" and cfg.P % 4 == 0 and args.layout == "matrix":
             out["algorithms"] = compare_algorithms(cfg, 40, 8)
     if not args.only_timed:
-        out["repeats"] = repeats(cfg, gemm=(cfg.name == "overlap"))
+        out["repeats"] = repeats(cfg, gemm={"none": False, "gemm": True, "alu": "alu"}[stand_in])
         out["local_step_alone"] = local_step_alone(cfg, args.steps, args.warmup)
     if not args.only_timed and args.layout == "matrix" and args.fusion is None:
         out["fusion_all"] = fusion_all_region(cfg, args.steps, args.warmup)
