@@ -668,16 +668,20 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
 #define DASGD_LAUNCH_ALL(WT, MEAN, MERGE)                                                                       \
     hipLaunchKernelGGL((k_step_all_flat<WT, MEAN, MERGE>), agrid, dim3(kWave), 0, c->main_s, x4, v4, g4, Ao, An, \
                        row4, c->W, c->lr, c->momentum, c->wd, om, inv_w)
+#define DASGD_LAUNCH_ROWS(WT, MERGE)                                                                            \
+    hipLaunchKernelGGL((k_step_all_rows<WT, MERGE>), agrid, dim3(kWave * WT), 0, c->main_s, x4, v4, g4, Ao, An,  \
+                       row4, c->lr, c->momentum, c->wd, om, inv_w)
 #define DASGD_LAUNCH_ALL_W(MEAN, MERGE)                                                                         \
     switch (c->W) {                                                                                             \
     case 1:  DASGD_LAUNCH_ALL(1, MEAN, MERGE);  break;                                                          \
-    case 2:  DASGD_LAUNCH_ALL(2, MEAN, MERGE);  break;                                                          \
-    case 4:  DASGD_LAUNCH_ALL(4, MEAN, MERGE);  break;                                                          \
-    case 8:  DASGD_LAUNCH_ALL(8, MEAN, MERGE);  break;                                                          \
-    case 16: DASGD_LAUNCH_ALL(16, MEAN, MERGE); break;                                                          \
+    case 2:  DASGD_LAUNCH_ROWS(2, MERGE);  break;                                                               \
+    case 4:  DASGD_LAUNCH_ROWS(4, MERGE);  break;                                                               \
+    case 8:  DASGD_LAUNCH_ROWS(8, MERGE);  break;                                                               \
+    case 16: DASGD_LAUNCH_ROWS(16, MERGE); break;                                                               \
     default: DASGD_LAUNCH_ALL(0, MEAN, MERGE);  break;                                                          \
     }
             if (fold) { DASGD_LAUNCH_ALL_W(true, true) } else { DASGD_LAUNCH_ALL_W(true, false) }
+#undef DASGD_LAUNCH_ROWS
 #undef DASGD_LAUNCH_ALL_W
 #undef DASGD_LAUNCH_ALL
         } else if (flat) {
