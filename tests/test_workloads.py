@@ -72,3 +72,15 @@ def test_quadratic_problem():
     assert torch.equal(qs.grad(x[idx], 2, 1, idx=idx), q.grad(x, 2, 1)[idx])
     g64 = q.grad(x.double(), 2, 1)
     assert g64.dtype == torch.float64 and torch.allclose(g64.float(), q.grad(x, 2, 1), atol=1e-6)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: asking for more must end with a message, not a run."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
