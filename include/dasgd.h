@@ -154,7 +154,7 @@ int dasgd_set_snapshot(dasgd_ctx *ctx, int mode);
 /* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
  * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots
  * (floor(d/tau)+1 slots of W x P' floats) and the averages (same number of slots of P' floats),
- * where P' pads every tensor to a multiple of 64 elements and adds 32.  Returns 0 on invalid
+ * where P' pads every tensor to a multiple of 64 elements and adds 256.  Returns 0 on invalid
  * arguments. */
 size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
 
@@ -171,6 +171,9 @@ size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t 
  *   main_stream, side_stream   hipStream_t handles; local step and merge run on main_stream,
  *              the W-way mean on side_stream.  Must be different streams of equal priority.
  * Copies the tables to the device and clears snapshots/averages (blocks until done).
+ * Every tensor and the workspace are checked against the extent of the device allocation that holds
+ * them, where the HIP runtime knows it: a tensor or workspace that would run past the end of its
+ * allocation is EINVAL (a kernel running past a buffer faults the GPU).
  * Errors: EINVAL, ENOMEM (workspace too small), ESTATE (already bound, or an earlier bind of this
  * context failed with EHIP: destroy it and create a new one), EHIP. */
 int dasgd_bind(dasgd_ctx *ctx, int n_tensors, const int64_t *numel,
@@ -199,9 +202,11 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
  * in the order given, one common row stride ld with P <= ld < P + 256 floats and ld a multiple of 4,
  * base 16-byte aligned -- the kernels address them by arithmetic alone (fastest; fastest of all when
- * ld is a multiple of 32, so that rows are 128-byte aligned to each other).  The up to 31 floats
- * between two rows are then padding that BELONGS TO THE MATRIX: the library reads and overwrites
- * them.  Any other layout goes through a chunk table.  Results are identical.
+ * ld is a multiple of 32, so that rows are 128-byte aligned to each other).  The up to 255 floats
+ * behind every row, the last one included, are then padding that BELONGS TO THE MATRIX: the library
+ * reads and overwrites them (if the allocation ends before the last row's padding does, the layout is
+ * not taken for a matrix).  Any other layout goes through a chunk table.  Results are identical.
+ * A changed gradient table is checked against its allocations like the tensors at dasgd_bind (EINVAL).
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
 int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
 

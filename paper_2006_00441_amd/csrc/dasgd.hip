@@ -199,6 +199,21 @@ bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const
     return true;
 }
 
+// False only when the runtime knows the allocation that holds p and [p, p + bytes) leaves it.  (Memory
+// the runtime cannot place -- not allocated through it -- cannot be checked and passes.)  A kernel that
+// runs past a buffer faults the GPU; a size mistake of the caller's is better met with an error code.
+bool range_ok(const void *p, size_t bytes)
+{
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;
+    }
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(base);
+    return a >= b && bytes <= size && a - b <= size - bytes;
+}
+
 inline float *snap_ptr(const dasgd_ctx *c, int slot)
 {
     return reinterpret_cast<float *>(c->ws + c->lay.S) + (size_t)slot * (size_t)c->W * (size_t)c->lay.P_pad;
@@ -486,10 +501,20 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         if (!x[r] || !v[r]) return DASGD_EINVAL;
         if ((reinterpret_cast<uintptr_t>(x[r]) | reinterpret_cast<uintptr_t>(v[r])) & 3u) return DASGD_EINVAL;
     }
+    for (size_t r = 0; r < rows; ++r) {
+        const size_t bytes = sizeof(float) * (size_t)numel[r % (size_t)n_tensors];
+        if (!range_ok(x[r], bytes) || !range_ok(v[r], bytes)) return DASGD_EINVAL;
+    }
     int64_t ldx = 0, ldv = 0;
-    const bool matrix = is_matrix(c, n_tensors, numel, x, &ldx) && is_matrix(c, n_tensors, numel, v, &ldv) && ldx == ldv;
+    bool matrix = is_matrix(c, n_tensors, numel, x, &ldx) && is_matrix(c, n_tensors, numel, v, &ldv) && ldx == ldv;
+    // the matrix kernels also touch the padding behind the LAST row: it must exist
+    if (matrix) {
+        const size_t extent = sizeof(float) * (size_t)c->W * (size_t)ldx;
+        matrix = range_ok(x[0], extent) && range_ok(v[0], extent);
+    }
     Layout L = make_layout(c, n_tensors, numel, matrix, ldx);
     if (workspace_bytes < L.total) return DASGD_ENOMEM;
+    if (!range_ok(workspace, L.total)) return DASGD_EINVAL;
 
     // chunk table
     std::vector<Chunk> chunks;
@@ -609,6 +634,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 if (!g[r] || (reinterpret_cast<uintptr_t>(g[r]) & 3u)) return DASGD_EINVAL;
             const bool changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
             if (changed) {
+                for (size_t r = 0; r < rows; ++r)
+                    if (!range_ok(g[r], sizeof(float) * (size_t)c->numel[r % (size_t)c->n_tensors])) return DASGD_EINVAL;
                 // retire the table in use (all kernels reading it are already enqueued), take the next
                 if (c->g_cur >= 0) {
                     HIPCHK(c, hipEventRecord(c->g_ev[c->g_cur], c->main_s));
@@ -625,7 +652,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 c->g_cached.assign(g, g + rows);
                 c->g_cur = b;
                 int64_t ldg = 0;
-                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g, &ldg) && ldg == c->ld;
+                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g, &ldg) && ldg == c->ld &&
+                              range_ok(g[0], sizeof(float) * (size_t)c->W * (size_t)ldg);
                 c->g0 = g[0];
             }
         }
@@ -862,6 +890,7 @@ int dasgd_gradient_average(dasgd_ctx *c, const float *G, float *out)
     if (!c->bound || c->dry) return DASGD_ESTATE;
     if (c->P % 4 != 0) return DASGD_EINVAL;
     if ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(out)) & 15u) return DASGD_EINVAL;
+    if (!range_ok(G, sizeof(float) * (size_t)c->W * (size_t)c->P) || !range_ok(out, sizeof(float) * (size_t)c->P)) return DASGD_EINVAL;
     int rec;
     int rc = prof_open(c, DASGD_K_MEAN, c->main_s, &rec);
     if (rc != DASGD_OK) return rc;

@@ -567,3 +567,39 @@ def test_full_size_overlap_with_foreign_work_equals_serial(schedule_name):
     assert torch.equal(outs[schedule_name], outs["SCHED_SERIAL"])
     ref = run_oracle(cfg, "f64", idx=idx)
     assert max_scaled_error(cfg, outs["SCHED_SERIAL"].numpy(), ref, idx) <= TOL
+
+
+# ------------------------------------------------------------------------------------------------
+# buffers that are too small for what the caller claims are refused, not overrun
+def test_buffers_shorter_than_claimed_are_refused():
+    import paper_2006_00441_amd as pkg
+    dev = torch.device("cuda:0")
+    torch.cuda.empty_cache()
+    n = 22 * 2**20 // 4 + 2**19               # 24 MiB: a fresh allocation of exactly this size
+    m, s = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+
+    def code(f):
+        with pytest.raises(pkg.DasgdError) as e:
+            f()
+        return e.value.code
+
+    x = torch.zeros(n, device=dev); v = torch.zeros(n, device=dev); g = torch.zeros(n, device=dev)
+    P = n + 4096                               # the caller claims more elements than the buffers hold
+    o = pkg.DaSGD(1, P, 1, 1, 0.1, 0.9, 0.0)
+    ws = torch.empty(o.workspace_bytes([P]) + 512, dtype=torch.uint8, device=dev)
+    wp = (ws.data_ptr() + 255) // 256 * 256
+    assert code(lambda: o.bind([P], [x.data_ptr()], [v.data_ptr()], wp, o.workspace_bytes([P]), m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    o.destroy()
+    # correct x and v, gradient buffer too short
+    o = pkg.DaSGD(1, n, 1, 1, 0.1, 0.9, 0.0)
+    ws = torch.empty(o.workspace_bytes([n]) + 512, dtype=torch.uint8, device=dev)
+    wp = (ws.data_ptr() + 255) // 256 * 256
+    o.bind([n], [x.data_ptr()], [v.data_ptr()], wp, o.workspace_bytes([n]), m.cuda_stream, s.cuda_stream)
+    assert code(lambda: o.local_step([g.data_ptr() + 4 * 8192])) == pkg.DASGD_EINVAL      # would end 32 KiB past the allocation
+    o.local_step([g.data_ptr()])
+    m.synchronize()
+    # workspace shorter than the size passed
+    o2 = pkg.DaSGD(1, n, 1, 1, 0.1, 0.9, 0.0)
+    assert code(lambda: o2.bind([n], [x.data_ptr()], [v.data_ptr()], wp + 2**22, o2.workspace_bytes([n]), m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    o2.destroy()
+    o.destroy()
