@@ -173,7 +173,8 @@ size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t 
  * Copies the tables to the device and clears snapshots/averages (blocks until done).
  * Every tensor and the workspace are checked against the extent of the device allocation that holds
  * them, where the HIP runtime knows it: a tensor or workspace that would run past the end of its
- * allocation is EINVAL (a kernel running past a buffer faults the GPU).
+ * allocation is EINVAL (a kernel running past a buffer faults the GPU).  So is any overlap among the
+ * x tensors, the v tensors and the workspace: all of them are written.
  * Errors: EINVAL, ENOMEM (workspace too small), ESTATE (already bound, or an earlier bind of this
  * context failed with EHIP: destroy it and create a new one), EHIP. */
 int dasgd_bind(dasgd_ctx *ctx, int n_tensors, const int64_t *numel,
@@ -206,7 +207,8 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * behind every row, the last one included, are then padding that BELONGS TO THE MATRIX: the library
  * reads and overwrites them (if the allocation ends before the last row's padding does, the layout is
  * not taken for a matrix).  Any other layout goes through a chunk table.  Results are identical.
- * A changed gradient table is checked against its allocations like the tensors at dasgd_bind (EINVAL).
+ * A changed gradient table is checked against its allocations like the tensors at dasgd_bind, and
+ * against x, v and the workspace for shared bytes (EINVAL); gradient buffers may alias each other.
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
 int dasgd_local_step(dasgd_ctx *ctx, const float *const *g);
 

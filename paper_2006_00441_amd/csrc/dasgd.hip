@@ -8,7 +8,9 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <deque>
+#include <utility>
 #include <new>
 #include <vector>
 
@@ -79,6 +81,7 @@ struct dasgd_ctx {
     hipStream_t main_s = nullptr, side_s = nullptr;
     // gradient pointer tables
     std::vector<const float *> g_cached;
+    std::vector<std::pair<uintptr_t, size_t>> owned;    // byte ranges of x, v and the workspace, sorted by start
     int g_cur = -1;
     void *g_pinned = nullptr;       // kGTables host staging tables (pinned)
     hipEvent_t g_ev[kGTables] = {};
@@ -212,6 +215,15 @@ bool range_ok(const void *p, size_t bytes)
     }
     const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(base);
     return a >= b && bytes <= size && a - b <= size - bytes;
+}
+
+// True if any two of the byte ranges [first, first + second) overlap (sorts its argument).
+bool any_overlap(std::vector<std::pair<uintptr_t, size_t>> &iv)
+{
+    std::sort(iv.begin(), iv.end());
+    for (size_t i = 1; i < iv.size(); ++i)
+        if (iv[i].first < iv[i - 1].first + iv[i - 1].second) return true;
+    return false;
 }
 
 inline float *snap_ptr(const dasgd_ctx *c, int slot)
@@ -505,6 +517,18 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         const size_t bytes = sizeof(float) * (size_t)numel[r % (size_t)n_tensors];
         if (!range_ok(x[r], bytes) || !range_ok(v[r], bytes)) return DASGD_EINVAL;
     }
+    {   // x, v and the workspace are all written: none of them may share a byte with another
+        std::vector<std::pair<uintptr_t, size_t>> iv;
+        iv.reserve(2 * rows + 1);
+        for (size_t r = 0; r < rows; ++r) {
+            const size_t bytes = sizeof(float) * (size_t)numel[r % (size_t)n_tensors];
+            iv.emplace_back(reinterpret_cast<uintptr_t>(x[r]), bytes);
+            iv.emplace_back(reinterpret_cast<uintptr_t>(v[r]), bytes);
+        }
+        iv.emplace_back(reinterpret_cast<uintptr_t>(workspace), workspace_bytes);
+        if (any_overlap(iv)) return DASGD_EINVAL;
+        c->owned.swap(iv);                     // sorted by start, pairwise disjoint: gradient buffers are checked against it
+    }
     int64_t ldx = 0, ldv = 0;
     bool matrix = is_matrix(c, n_tensors, numel, x, &ldx) && is_matrix(c, n_tensors, numel, v, &ldv) && ldx == ldv;
     // the matrix kernels also touch the padding behind the LAST row: it must exist
@@ -634,8 +658,15 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 if (!g[r] || (reinterpret_cast<uintptr_t>(g[r]) & 3u)) return DASGD_EINVAL;
             const bool changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
             if (changed) {
-                for (size_t r = 0; r < rows; ++r)
-                    if (!range_ok(g[r], sizeof(float) * (size_t)c->numel[r % (size_t)c->n_tensors])) return DASGD_EINVAL;
+                for (size_t r = 0; r < rows; ++r) {
+                    const size_t bytes = sizeof(float) * (size_t)c->numel[r % (size_t)c->n_tensors];
+                    if (!range_ok(g[r], bytes)) return DASGD_EINVAL;
+                    // a gradient buffer that shares bytes with x, v or the workspace would be overwritten while it is read
+                    const uintptr_t a = reinterpret_cast<uintptr_t>(g[r]);
+                    auto it = std::upper_bound(c->owned.begin(), c->owned.end(), std::make_pair(a, ~(size_t)0));
+                    if (it != c->owned.end() && it->first < a + bytes) return DASGD_EINVAL;
+                    if (it != c->owned.begin() && (it - 1)->first + (it - 1)->second > a) return DASGD_EINVAL;
+                }
                 // retire the table in use (all kernels reading it are already enqueued), take the next
                 if (c->g_cur >= 0) {
                     HIPCHK(c, hipEventRecord(c->g_ev[c->g_cur], c->main_s));

@@ -336,10 +336,16 @@ def test_bind_rejects_bad_arguments():
     assert code(lambda: o.bind([P], [0] + xp[1:], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
     assert code(lambda: o.bind([P], [xp[0] + 2] + xp[1:], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
     assert code(lambda: o.bind([P - 1], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    # buffers that share bytes: momentum on top of the weights, two replicas on one buffer, weights inside the workspace
+    assert code(lambda: o.bind([P], xp, xp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P], [xp[0], xp[0] + 16], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    assert code(lambda: o.bind([P], [ws.data_ptr() + 256, xp[1]], vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
     o.bind([P], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)
     assert code(lambda: o.bind([P], xp, vp, ws.data_ptr(), need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_ESTATE
     assert code(lambda: o.local_step(None)) == pkg.DASGD_EINVAL            # no gradient table yet
     assert code(lambda: o.local_step([0, 0])) == pkg.DASGD_EINVAL          # null gradient pointers
+    assert code(lambda: o.local_step([xp[0], vp[1]])) == pkg.DASGD_EINVAL  # gradients on top of weights / momentum
+    assert code(lambda: o.local_step([ws.data_ptr() + 4096, vp[1] + 64])) == pkg.DASGD_EINVAL
     assert o.query()[0] == -1                                              # nothing ran
     g = [[torch.zeros(P, device=dev)] for _ in range(W)]
     o.step([t.data_ptr() for r in g for t in r])
