@@ -300,6 +300,12 @@ int dasgd_set_band(dasgd_ctx *ctx, int log_band);
  * NULL.  ESTATE if not bound. */
 int dasgd_band(dasgd_ctx *ctx, int kernel, int *log_band, int *settled, int *trials);
 
+/* The extent check of dasgd_bind, for callers and tests: *bytes_to_end = number of bytes from p to the
+ * end of the device allocation that holds it, as the HIP runtime knows it (a framework's caching
+ * allocator may have carved p out of a larger allocation: the figure is an upper bound on what belongs
+ * to the caller).  EINVAL if p is NULL or not inside an allocation the runtime knows. */
+int dasgd_device_extent(const void *p, size_t *bytes_to_end);
+
 /* Host-only self-check of the index arithmetic behind that work order, with the very function the
  * kernels use: for a W x (4*row4)-float matrix and band length 2^log_band (clamped as the library
  * would), every aligned 64-column block of the flat index space must be handled by exactly one

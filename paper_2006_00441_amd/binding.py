@@ -59,6 +59,7 @@ EXPORTS = {
     "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64, _pi64]),
     "dasgd_set_band": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_band": (ctypes.c_int, [_vp, ctypes.c_int, _pint, _pint, _pint]),
+    "dasgd_device_extent": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
     "dasgd_check_block_map": (ctypes.c_int, [ctypes.c_int, _i64, ctypes.c_int]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
@@ -108,6 +109,15 @@ def choose_delay(t_c: float, t_p: float) -> Tuple[int, int]:
     if rc < 0:
         raise DasgdError("dasgd_choose_delay", rc)
     return int(d.value), int(tau.value)
+
+
+def device_extent(ptr: int) -> int:
+    """Bytes from ptr to the end of the device allocation that holds it (dasgd_device_extent)."""
+    n = ctypes.c_size_t()
+    rc = lib().dasgd_device_extent(ctypes.c_void_p(int(ptr)), ctypes.byref(n))
+    if rc < 0:
+        raise DasgdError("dasgd_device_extent", rc)
+    return int(n.value)
 
 
 def check_block_map(W: int, row4: int, log_band: int) -> int:

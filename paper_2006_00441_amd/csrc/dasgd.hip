@@ -1031,6 +1031,19 @@ int dasgd_band(dasgd_ctx *c, int kernel, int *log_band, int *settled, int *trial
     return DASGD_OK;
 }
 
+int dasgd_device_extent(const void *p, size_t *bytes_to_end)
+{
+    if (!p || !bytes_to_end) return DASGD_EINVAL;
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
+        (void)hipGetLastError();
+        return DASGD_EINVAL;
+    }
+    *bytes_to_end = size - (size_t)(reinterpret_cast<uintptr_t>(p) - reinterpret_cast<uintptr_t>(base));
+    return DASGD_OK;
+}
+
 int dasgd_check_block_map(int W, int64_t row4, int log_band)
 {
     if (W < 1 || W > 65535 || row4 < 64 || log_band < 0 || log_band > 11) return DASGD_EINVAL;

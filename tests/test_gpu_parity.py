@@ -578,10 +578,11 @@ def test_full_size_overlap_with_foreign_work_equals_serial(schedule_name):
 # ------------------------------------------------------------------------------------------------
 # buffers that are too small for what the caller claims are refused, not overrun
 def test_buffers_shorter_than_claimed_are_refused():
+    """Claims are sized from the extent the runtime reports for each buffer's allocation, so the test
+    does not depend on how the framework's caching allocator carves its segments."""
     import paper_2006_00441_amd as pkg
     dev = torch.device("cuda:0")
-    torch.cuda.empty_cache()
-    n = 22 * 2**20 // 4 + 2**19               # 24 MiB: a fresh allocation of exactly this size
+    n = 6 * 2**20
     m, s = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
 
     def code(f):
@@ -590,22 +591,29 @@ def test_buffers_shorter_than_claimed_are_refused():
         return e.value.code
 
     x = torch.zeros(n, device=dev); v = torch.zeros(n, device=dev); g = torch.zeros(n, device=dev)
-    P = n + 4096                               # the caller claims more elements than the buffers hold
+    assert pkg.device_extent(x.data_ptr()) >= 4 * n and pkg.device_extent(x.data_ptr() + 4096) == pkg.device_extent(x.data_ptr()) - 4096
+    with pytest.raises(pkg.DasgdError):
+        pkg.device_extent(0)
+    # the caller claims more elements than the allocation behind x can hold
+    P = pkg.device_extent(x.data_ptr()) // 4 + 4096
     o = pkg.DaSGD(1, P, 1, 1, 0.1, 0.9, 0.0)
-    ws = torch.empty(o.workspace_bytes([P]) + 512, dtype=torch.uint8, device=dev)
-    wp = (ws.data_ptr() + 255) // 256 * 256
-    assert code(lambda: o.bind([P], [x.data_ptr()], [v.data_ptr()], wp, o.workspace_bytes([P]), m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    need = o.workspace_bytes([P])
+    assert code(lambda: o.bind([P], [x.data_ptr()], [v.data_ptr()], 256, need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
     o.destroy()
-    # correct x and v, gradient buffer too short
+    # correct x and v; gradient buffer handed over so late in its allocation that n elements do not fit
     o = pkg.DaSGD(1, n, 1, 1, 0.1, 0.9, 0.0)
-    ws = torch.empty(o.workspace_bytes([n]) + 512, dtype=torch.uint8, device=dev)
+    need = o.workspace_bytes([n])
+    ws = torch.empty(need + 512, dtype=torch.uint8, device=dev)
     wp = (ws.data_ptr() + 255) // 256 * 256
-    o.bind([n], [x.data_ptr()], [v.data_ptr()], wp, o.workspace_bytes([n]), m.cuda_stream, s.cuda_stream)
-    assert code(lambda: o.local_step([g.data_ptr() + 4 * 8192])) == pkg.DASGD_EINVAL      # would end 32 KiB past the allocation
+    o.bind([n], [x.data_ptr()], [v.data_ptr()], wp, need, m.cuda_stream, s.cuda_stream)
+    late = g.data_ptr() + (pkg.device_extent(g.data_ptr()) - 4 * n + 4096)
+    assert code(lambda: o.local_step([late])) == pkg.DASGD_EINVAL
     o.local_step([g.data_ptr()])
     m.synchronize()
-    # workspace shorter than the size passed
+    # workspace handed over so late in its allocation that the size passed does not fit
     o2 = pkg.DaSGD(1, n, 1, 1, 0.1, 0.9, 0.0)
-    assert code(lambda: o2.bind([n], [x.data_ptr()], [v.data_ptr()], wp + 2**22, o2.workspace_bytes([n]), m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
+    x2 = torch.zeros(n, device=dev); v2 = torch.zeros(n, device=dev)
+    late_ws = (wp + (pkg.device_extent(wp) - need + 256) + 255) // 256 * 256
+    assert code(lambda: o2.bind([n], [x2.data_ptr()], [v2.data_ptr()], late_ws, need, m.cuda_stream, s.cuda_stream)) == pkg.DASGD_EINVAL
     o2.destroy()
     o.destroy()
