@@ -781,10 +781,12 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
             float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
             const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
-            const dim3 grid((unsigned)c->lay.n_chunks, (unsigned)c->W);
+            // folded merge: the W replicas of a chunk back to back on one XCD (one-dimensional grid)
+            const dim3 grid = fold ? dim3((unsigned)((c->lay.n_chunks + 7) / 8 * 8 * c->W))
+                                   : dim3((unsigned)c->lay.n_chunks, (unsigned)c->W);
 #define DASGD_LAUNCH_TABLE(MODE, MERGE)                                                                         \
     hipLaunchKernelGGL((k_local_step<MODE, MERGE>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, \
-                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om)
+                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om, c->W, (int)c->lay.n_chunks)
             if (fold && mode == kStoreX)       DASGD_LAUNCH_TABLE(kStoreX, true);
             else if (fold)                     DASGD_LAUNCH_TABLE(kStoreXS, true);
             else if (mode == kStoreX)          DASGD_LAUNCH_TABLE(kStoreX, false);
