@@ -286,7 +286,10 @@ int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *ti
  * first 16 launches of such a kernel rotate through five lengths, three launches of each bracketed
  * by timing events on main_stream; finished events are collected without waiting at later launches,
  * and the fastest length is kept from then on.  The order never changes results: every element is
- * computed by the same arithmetic whichever workgroup handles it (bit-identical, tested).
+ * computed by the same arithmetic whichever workgroup handles it (bit-identical, tested).  The
+ * chunk-table kernel (other layouts) has two orders for a folded merge -- replica after replica, or
+ * the W replicas of a chunk back to back on one L2 partition -- and is measured the same way; a fixed
+ * log_band selects the second.
  *   log_band  -1: measure (default);  0..11: use this length (clamped to the row length).
  * May be called at any time.  EINVAL outside -1..11.  A caller that captures the step calls into a HIP
  * graph fixes the length first (the measurement queries events, which a capturing stream forbids) --

@@ -107,6 +107,8 @@ struct dasgd_ctx {
     const float *g0 = nullptr;
     int band_fixed = -1;            // >= 0: log2 of the band length set by the caller; -1: measured (BandTuner)
     BandTuner tuner[DASGD_K_COUNT];
+    BandTuner table_tuner[2];       // chunk-table local step with a folded merge (0: no snapshot store, 1: with):
+                                    // candidates -1 (replica-major grid) and 0 (replicas of a chunk on one XCD)
     bool idx32 = false;             // 64 <= P/4 and W*P/4 + 64 < 2^31: the column-aware flat kernels apply
                                     // (32-bit indices; a 64-element block spans at most two rows)
     std::deque<Pending> pending;
@@ -319,20 +321,20 @@ int band_decide(dasgd_ctx *c, BandTuner &t)
     return DASGD_OK;
 }
 
-// Band length for the next launch of kernel kind `kid` over rows of row4 128-bit columns.  *trial >= 0:
-// the launch is a timed trial, band_close must follow it.
-int band_pick(dasgd_ctx *c, int kid, unsigned row4, unsigned *log_band, int *trial)
+// Choice for the next launch of the kernel that tuner t serves, over rows of row4 128-bit columns: the
+// log2 of a band length, or a negative candidate (the caller's other work order).  *trial >= 0: the
+// launch is a timed trial, band_close must follow it.
+int band_pick(dasgd_ctx *c, BandTuner &t, unsigned row4, int *log_band, int *trial)
 {
     *trial = -1;
     if (c->band_fixed >= 0) {
-        *log_band = decode_clamp_log_band(row4, (unsigned)c->band_fixed);
+        *log_band = (int)decode_clamp_log_band(row4, (unsigned)c->band_fixed);
         return DASGD_OK;
     }
-    BandTuner &t = c->tuner[kid];
     if (t.n_cand == 0) {                        // fit the candidates to the row length, drop duplicates
         int n = 0;
         for (int i = 0; i < BandTuner::kMaxCand; ++i) {
-            const int lb = (int)decode_clamp_log_band(row4, (unsigned)t.cand[i]);
+            const int lb = t.cand[i] < 0 ? t.cand[i] : (int)decode_clamp_log_band(row4, (unsigned)t.cand[i]);
             bool dup = false;
             for (int k = 0; k < n; ++k) dup = dup || t.cand[k] == lb;
             if (!dup) t.cand[n++] = lb;
@@ -345,7 +347,7 @@ int band_pick(dasgd_ctx *c, int kid, unsigned row4, unsigned *log_band, int *tri
         if (rc != DASGD_OK) return rc;
     }
     if (t.chosen >= 0) {
-        *log_band = (unsigned)t.cand[t.chosen];
+        *log_band = t.cand[t.chosen];
         return DASGD_OK;
     }
     const int64_t n = t.launches++;
@@ -354,7 +356,7 @@ int band_pick(dasgd_ctx *c, int kid, unsigned row4, unsigned *log_band, int *tri
         for (int i = 0; i < t.n_cand; ++i)
             if (t.issued[i] < BandTuner::kSamples && (pick < 0 || t.issued[i] < t.issued[pick])) pick = i;
     if (pick < 0) {                             // cold launch, or all trials issued and results still to come
-        *log_band = (unsigned)t.cand[0];
+        *log_band = t.cand[0];
         return DASGD_OK;
     }
     BandTuner::Rec r;
@@ -366,14 +368,14 @@ int band_pick(dasgd_ctx *c, int kid, unsigned row4, unsigned *log_band, int *tri
     HIPCHK(c, hipEventRecord(r.start, c->main_s));
     t.inflight.push_back(r);
     t.issued[pick] += 1;
-    *log_band = (unsigned)t.cand[pick];
+    *log_band = t.cand[pick];
     *trial = pick;
     return DASGD_OK;
 }
-int band_close(dasgd_ctx *c, int kid, int trial)
+int band_close(dasgd_ctx *c, BandTuner &t, int trial)
 {
     if (trial < 0) return DASGD_OK;
-    HIPCHK(c, hipEventRecord(c->tuner[kid].inflight.back().stop, c->main_s));
+    HIPCHK(c, hipEventRecord(t.inflight.back().stop, c->main_s));
     return DASGD_OK;
 }
 
@@ -425,6 +427,10 @@ dasgd_ctx *dasgd_create(int W, int64_t P, int d, int tau, float lr, float moment
     c->W = W; c->P = P; c->d = d; c->tau = tau;
     c->lr = lr; c->momentum = momentum; c->wd = wd;
     c->slots = d / tau + 1;
+    for (BandTuner &t : c->table_tuner) {
+        const int orders[BandTuner::kMaxCand] = {-1, 0, 0, 0, 0};          // duplicates are dropped when the tuner starts
+        for (int i = 0; i < BandTuner::kMaxCand; ++i) t.cand[i] = orders[i];
+    }
     return c;
 }
 
@@ -713,6 +719,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
         int rec, trial = -1;
+        BandTuner *tuned = nullptr;
         int rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         const bool flat = c->xv_matrix && c->g_matrix && (!fold || c->idx32);
@@ -751,9 +758,11 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             if (fold) {
                 const v4f *A4 = reinterpret_cast<const v4f *>(A);
                 const unsigned row4 = (unsigned)(c->ld / 4);
-                unsigned lb;
-                rc = band_pick(c, kid, row4, &lb, &trial);
+                int lbi;
+                tuned = &c->tuner[kid];
+                rc = band_pick(c, *tuned, row4, &lbi, &trial);
                 if (rc != DASGD_OK) return rc;
+                const unsigned lb = (unsigned)lbi;
                 const dim3 fgrid((unsigned)decode_grid((unsigned)c->W, row4, lb));
 #define DASGD_LAUNCH_FOLD(SNAP, WT)                                                                             \
     hipLaunchKernelGGL((k_step_merge_flat<SNAP, WT>), fgrid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4,     \
@@ -781,12 +790,23 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
             float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
             const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
-            // folded merge: the W replicas of a chunk back to back on one XCD (one-dimensional grid)
-            const dim3 grid = fold ? dim3((unsigned)((c->lay.n_chunks + 7) / 8 * 8 * c->W))
-                                   : dim3((unsigned)c->lay.n_chunks, (unsigned)c->W);
+            // Folded merge: either replica-major (all chunks of replica 0, then of replica 1, ...: each
+            // replica streams linearly and A is re-read W times, which is cheap while A fits the Infinity
+            // Cache), or the W replicas of a chunk back to back on one XCD (A from HBM once).  Which is
+            // faster depends on the size of A and on how the allocations lie in memory: measured in place.
+            int xcd_order = 0;
+            if (fold) {
+                tuned = &c->table_tuner[mode == kStoreX ? 0 : 1];
+                int pick;
+                rc = band_pick(c, *tuned, 1u << 20, &pick, &trial);
+                if (rc != DASGD_OK) return rc;
+                xcd_order = pick >= 0 ? 1 : 0;
+            }
+            const dim3 grid = xcd_order ? dim3((unsigned)((c->lay.n_chunks + 7) / 8 * 8 * c->W))
+                                        : dim3((unsigned)c->lay.n_chunks, (unsigned)c->W);
 #define DASGD_LAUNCH_TABLE(MODE, MERGE)                                                                         \
     hipLaunchKernelGGL((k_local_step<MODE, MERGE>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, \
-                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om, c->W, (int)c->lay.n_chunks)
+                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om, c->W, (int)c->lay.n_chunks, xcd_order)
             if (fold && mode == kStoreX)       DASGD_LAUNCH_TABLE(kStoreX, true);
             else if (fold)                     DASGD_LAUNCH_TABLE(kStoreXS, true);
             else if (mode == kStoreX)          DASGD_LAUNCH_TABLE(kStoreX, false);
@@ -795,8 +815,10 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
 #undef DASGD_LAUNCH_TABLE
         }
         HIPCHK(c, hipGetLastError());
-        rc = band_close(c, kid, trial);
-        if (rc != DASGD_OK) return rc;
+        if (tuned) {
+            rc = band_close(c, *tuned, trial);
+            if (rc != DASGD_OK) return rc;
+        }
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
     }
@@ -858,9 +880,10 @@ int dasgd_merge(dasgd_ctx *c)
             const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
             const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
             const unsigned n4 = (unsigned)(row4 * c->W);
-            unsigned lb;
-            rc = band_pick(c, DASGD_K_MERGE, (unsigned)row4, &lb, &trial);
+            int lbi;
+            rc = band_pick(c, c->tuner[DASGD_K_MERGE], (unsigned)row4, &lbi, &trial);
             if (rc != DASGD_OK) return rc;
+            const unsigned lb = (unsigned)lbi;
             const dim3 grid((unsigned)decode_grid((unsigned)c->W, (unsigned)row4, lb));
             switch (c->W) {
             case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
@@ -880,7 +903,7 @@ int dasgd_merge(dasgd_ctx *c)
                 hipLaunchKernelGGL((k_merge<false>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
         }
         HIPCHK(c, hipGetLastError());
-        rc = band_close(c, DASGD_K_MERGE, trial);
+        rc = band_close(c, c->tuner[DASGD_K_MERGE], trial);
         if (rc != DASGD_OK) return rc;
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
@@ -1084,10 +1107,12 @@ void dasgd_destroy(dasgd_ctx *c)
         for (int b = 0; b < kGTables; ++b) if (c->g_ev[b]) (void)hipEventDestroy(c->g_ev[b]);
         for (const ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
         for (const ProfRec &r : c->prof_pool) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-        for (BandTuner &t : c->tuner) {
-            for (const BandTuner::Rec &r : t.inflight) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-            for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
-        }
+        for (BandTuner *ts : {c->tuner, c->table_tuner})
+            for (int i = 0; i < (ts == c->tuner ? (int)DASGD_K_COUNT : 2); ++i) {
+                BandTuner &t = ts[i];
+                for (const BandTuner::Rec &r : t.inflight) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+                for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
+            }
         if (c->g_pinned) (void)hipHostFree(c->g_pinned);
     }
     delete c;

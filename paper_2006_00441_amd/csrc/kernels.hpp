@@ -90,20 +90,20 @@ __device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
 // Local step on every replica through the chunk table: grid = (chunks, W).
 // 20 bytes per element (24 when both x and the snapshot are stored).
 // MERGE: this step's merge is folded in -- the value stored to x is y + om (A - y), the snapshot
-// (if any) still receives y (paper Eq. 2, both branches in one pass).  The grid is then one-dimensional
-// and ordered so that the W replicas of a chunk run back to back on one XCD:
-// the chunk's piece of A comes from HBM once and from that XCD's L2 for the other W-1 replicas.
+// (if any) still receives y (paper Eq. 2, both branches in one pass).  With xcd_order the grid is
+// one-dimensional and ordered so that the W replicas of a chunk run back to back on one XCD: the
+// chunk's piece of A comes from HBM once and from that XCD's L2 for the other W-1 replicas.
 template <int MODE, bool MERGE>
 __global__ void __launch_bounds__(kThreads)
 k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, float *const *__restrict__ vp,
              const float *const *__restrict__ gp, float *__restrict__ S, int64_t P_pad, int n_tensors,
-             float lr, float momentum, float wd, const float *__restrict__ A, float om, int W, int n_chunks)
+             float lr, float momentum, float wd, const float *__restrict__ A, float om, int W, int n_chunks, int xcd_order)
 {
     constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
     static_assert(!(MERGE && MODE == kStoreS), "a folded merge always stores x");
     unsigned chunk_id = blockIdx.x;
     int j = blockIdx.y;
-    if (MERGE) {
+    if (MERGE && xcd_order) {
         const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
         j = (int)(slot % (unsigned)W);
         chunk_id = (slot / (unsigned)W) * 8u + xcd;

@@ -507,14 +507,16 @@ def pkg_kernel_names():
 # band order of the column-aware kernels: any band length, and the in-place measurement, give the same bits
 @pytest.mark.parametrize("fusion,snapshot", [(2, 1), (2, 0), (0, 0), (1, 0)])
 @pytest.mark.parametrize("tau,d", [(1, 2), (3, 1)])
-@pytest.mark.parametrize("W,numel", [(8, [64 * 4 * 37 + 12, 1000, 36]), (3, [4096 * 5]), (5, [260])])
-def test_band_length_never_changes_results(W, numel, fusion, snapshot, tau, d):
-    """Fixed band lengths, and the measuring mode (-1), which rotates through band lengths while it
+@pytest.mark.parametrize("W,numel,layout", [(8, [64 * 4 * 37 + 12, 1000, 36], "arena"), (3, [4096 * 5], "arena"), (5, [260], "arena"),
+                                            (8, [4096 * 3 + 100, 5000, 36], "separate")])
+def test_band_length_never_changes_results(W, numel, layout, fusion, snapshot, tau, d):
+    """Fixed band lengths, and the measuring mode (-1), which rotates through band lengths (matrix
+    layout) or through the two block orders of the chunk-table kernel (separate tensors) while it
     measures."""
     cfg = small(tau=tau, d=d, W=W, steps=24, params=custom_param_set(numel))
     outs = {}
     for band in (-1, 0, 1, 3, 8, 11):
-        run = GpuRun(cfg, fusion=fusion, snapshot=snapshot)
+        run = GpuRun(cfg, layout=layout, fusion=fusion, snapshot=snapshot)
         run.opt.set_band(band)
         for _ in range(cfg.steps):
             run.step()
