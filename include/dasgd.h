@@ -75,9 +75,9 @@ enum {
     DASGD_FUSE_STEP_MERGE = 2, /* default: when a merge is due at the step being taken (and d > 0), the local
                                   step applies it in the same pass (Eq. 2, both branches at once) and
                                   dasgd_merge only retires the average; otherwise as DASGD_FUSE_SNAPSHOT */
-    DASGD_FUSE_ALL        = 3  /* the mean is computed by the local-step kernel too (one lane updates one
-                                  column of all W replicas): no snapshot, no mean kernel, nothing on the
-                                  side stream; dasgd_average_begin and dasgd_merge only keep the books.
+    DASGD_FUSE_ALL        = 3  /* the mean is computed by the local-step kernel too (a workgroup updates a
+                                  window of columns of all W replicas and sums the new values through
+                                  LDS): no snapshot, no mean kernel, nothing on the side stream; dasgd_average_begin and dasgd_merge only keep the books.
                                   What one GPU can do when the average need not be a separate,
                                   overlappable operation.  Needs the W x P matrix layout and d > 0;
                                   otherwise behaves as DASGD_FUSE_STEP_MERGE */
