@@ -532,12 +532,14 @@ def main() -> int:
     wall, ev_ms, kernels, tuning = timed_region(cfg, args.steps, args.warmup,
                                                 gemm={"none": False, "gemm": True, "alu": "alu"}[stand_in])
     ms_per_step = wall / args.steps * 1e3
-    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     for name, k in kernels.items():
         b = algorithmic_bytes_per_rp(name, cfg.W) * rp
         k["algorithmic_bytes"] = b
         k["GBps"] = b / (k["avg_ms"] * 1e-3) / 1e9
         k["frac_of_hbm_peak"] = k["GBps"] / HBM_PEAK_GBS
+    # the dominant kernel is the one that moves the most bytes over the run (a side-stream kernel that sits
+    # behind a stand-in of the caller's looks long by the clock without being the one that does the work)
+    dom = max(kernels, key=lambda k: kernels[k]["algorithmic_bytes"] * kernels[k]["launches"])
     d = kernels[dom]
     out = {
         "metric": "replica-params updated/s + achieved HBM GB/s; % averaging time hidden",
