@@ -96,7 +96,9 @@ enum {
                                      amplified by 1/xi: measured against an fp64 run, about 1.6 times the
                                      deviation of the copy mode, both growing like the square root of the
                                      step count and below 1e-5 of the weight scale up to 3000 steps at
-                                     xi = 0.25).  Used when: matrix layout;
+                                     xi = 0.25).  The library's own kernels wait; a caller whose OWN kernels
+                                     write x between two steps (clipping, loading a checkpoint) must first
+                                     wait for side_stream, or use the copy mode.  Used when: matrix layout;
                                      schedule OVERLAP or SERIAL; fusion level 2; and either no merge falls
                                      on the step or xi >= 1/8.  Otherwise the copy is made. */
 };
