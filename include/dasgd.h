@@ -201,7 +201,9 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * for this step have been issued (in stream order), and not necessarily between them.
  *   g   [W * n_tensors] host array of device pointers (same order and shapes as x), read only;
  *       the buffers must stay valid and unchanged until the kernel has run.  NULL re-uses the
- *       pointers of the previous call (the table is re-uploaded only when it changes).
+ *       pointers of the previous call (the table is re-uploaded only when it changes; four device
+ *       copies are used in rotation, so a caller that changes it at every step can run at most three
+ *       changes ahead of the GPU before this call waits).
  * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
  * in the order given, one common row stride ld with P <= ld < P + 256 floats and ld a multiple of 4,
  * base 16-byte aligned -- the kernels address them by arithmetic alone (fastest; fastest of all when

@@ -207,16 +207,30 @@ bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const
 // False only when the runtime knows the allocation that holds p and [p, p + bytes) leaves it.  (Memory
 // the runtime cannot place -- not allocated through it -- cannot be checked and passes.)  A kernel that
 // runs past a buffer faults the GPU; a size mistake of the caller's is better met with an error code.
-bool range_ok(const void *p, size_t bytes)
-{
-    hipDeviceptr_t base = nullptr;
+// `last` remembers the allocation found for the previous pointer of the same pass: tensors usually
+// sit side by side in one allocation, and asking the runtime costs about half a microsecond each time.
+struct DeviceRange {
+    uintptr_t base = 0;
     size_t size = 0;
-    if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
-        (void)hipGetLastError();
-        return true;
+};
+bool range_ok(const void *p, size_t bytes, DeviceRange *last = nullptr)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+    DeviceRange r;
+    if (last && last->size && a >= last->base && a - last->base < last->size) {
+        r = *last;
+    } else {
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
+            (void)hipGetLastError();
+            return true;
+        }
+        r.base = reinterpret_cast<uintptr_t>(base);
+        r.size = size;
+        if (last) *last = r;
     }
-    const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(base);
-    return a >= b && bytes <= size && a - b <= size - bytes;
+    return a >= r.base && bytes <= r.size && a - r.base <= r.size - bytes;
 }
 
 // True if any two of the byte ranges [first, first + second) overlap (sorts its argument).
@@ -519,9 +533,12 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         if (!x[r] || !v[r]) return DASGD_EINVAL;
         if ((reinterpret_cast<uintptr_t>(x[r]) | reinterpret_cast<uintptr_t>(v[r])) & 3u) return DASGD_EINVAL;
     }
-    for (size_t r = 0; r < rows; ++r) {
-        const size_t bytes = sizeof(float) * (size_t)numel[r % (size_t)n_tensors];
-        if (!range_ok(x[r], bytes) || !range_ok(v[r], bytes)) return DASGD_EINVAL;
+    {
+        DeviceRange lx, lv;
+        for (size_t r = 0; r < rows; ++r) {
+            const size_t bytes = sizeof(float) * (size_t)numel[r % (size_t)n_tensors];
+            if (!range_ok(x[r], bytes, &lx) || !range_ok(v[r], bytes, &lv)) return DASGD_EINVAL;
+        }
     }
     {   // x, v and the workspace are all written: none of them may share a byte with another
         std::vector<std::pair<uintptr_t, size_t>> iv;
@@ -664,9 +681,10 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                 if (!g[r] || (reinterpret_cast<uintptr_t>(g[r]) & 3u)) return DASGD_EINVAL;
             const bool changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
             if (changed) {
+                DeviceRange lg;
                 for (size_t r = 0; r < rows; ++r) {
                     const size_t bytes = sizeof(float) * (size_t)c->numel[r % (size_t)c->n_tensors];
-                    if (!range_ok(g[r], bytes)) return DASGD_EINVAL;
+                    if (!range_ok(g[r], bytes, &lg)) return DASGD_EINVAL;
                     // a gradient buffer that shares bytes with x, v or the workspace would be overwritten while it is read
                     const uintptr_t a = reinterpret_cast<uintptr_t>(g[r]);
                     auto it = std::upper_bound(c->owned.begin(), c->owned.end(), std::make_pair(a, ~(size_t)0));
