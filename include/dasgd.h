@@ -18,7 +18,8 @@
  *     PyTorch); the library allocates no device memory.  All pointer ARRAYS are host memory.
  *   - Streams are raw hipStream_t handles passed as void*; the caller owns them.
  *   - Every step call only enqueues work and returns; only dasgd_bind (set-up copies),
- *     dasgd_profile_read and dasgd_destroy block the host.
+ *     dasgd_profile_read and dasgd_destroy block the host (and dasgd_local_step when the gradient
+ *     pointer table has changed four times while the GPU still works on the oldest of them).
  *   - A context is not thread-safe.  Functions return DASGD_OK or a negative error code and
  *     leave the context unchanged on error.
  *   - k denotes the 0-based index of the most recently completed local step.
