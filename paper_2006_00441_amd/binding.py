@@ -130,8 +130,10 @@ def check_block_map(W: int, row4: int, log_band: int) -> int:
 
 
 def _ptr_array(ptrs: Sequence[int]):
-    arr = (ctypes.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
-    return arr
+    """Pointers as a C array of void*; an array made earlier (DaSGD.grad_pointers) is passed through."""
+    if isinstance(ptrs, ctypes.Array):
+        return ptrs
+    return (ctypes.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
 
 
 class DaSGD:
@@ -321,5 +323,7 @@ class DaSGD:
         return ws
 
     @staticmethod
-    def grad_pointers(g: Sequence[Sequence["torch.Tensor"]]) -> List[int]:
-        return [t.data_ptr() for rep in g for t in rep]
+    def grad_pointers(g: Sequence[Sequence["torch.Tensor"]]):
+        """The gradient table of local_step/step, marshalled once: W*n_tensors device pointers,
+        replica-major, as a C array that can be passed at every step without being rebuilt."""
+        return _ptr_array([t.data_ptr() for rep in g for t in rep])
