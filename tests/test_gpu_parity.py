@@ -662,3 +662,23 @@ def test_serial_steps_replay_from_a_hip_graph():
         scratch.add_(1.0)                            # the program's own eager work between replays
         torch.cuda.synchronize()
     run.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# randomly drawn problems (sizes, replicas, schedule, settings) against the fp64 oracle
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=50, deadline=None, derandomize=True)
+@given(W=st.sampled_from([1, 2, 3, 4, 7, 8, 16, 19]), tau=st.integers(1, 5), d=st.integers(0, 6),
+       xi=st.sampled_from([0.0, 0.125, 0.25, 0.6, 1.0]),
+       sizes=st.lists(st.one_of(st.integers(1, 300), st.integers(4000, 9000)), min_size=1, max_size=4),
+       pad_to_4=st.booleans(), layout=st.sampled_from(["arena", "arena_padded", "separate"]),
+       fusion=st.integers(0, 3), snapshot=st.integers(0, 1), schedule=st.sampled_from([0, 1, 3]))
+def test_random_configurations_match_oracle(W, tau, d, xi, sizes, pad_to_4, layout, fusion, snapshot, schedule):
+    if pad_to_4:                                    # make the total a multiple of 4: the matrix kernels then apply
+        sizes = sizes[:-1] + [sizes[-1] + (-sum(sizes)) % 4]
+    cfg = small(tau=tau, d=d, W=W, xi=xi, steps=2 * tau + d + 5, params=custom_param_set(sizes))
+    x = run_gpu(cfg, layout=layout, fusion=fusion, snapshot=snapshot, schedule=schedule)
+    err = max_scaled_error(cfg, x, run_oracle(cfg, "f64"))
+    assert err <= TOL, (err, W, tau, d, xi, sizes, layout, fusion, snapshot, schedule)
