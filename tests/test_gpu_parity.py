@@ -669,7 +669,7 @@ def test_serial_steps_replay_from_a_hip_graph():
 from hypothesis import given, settings, strategies as st  # noqa: E402
 
 
-@settings(max_examples=50, deadline=None, derandomize=True)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(W=st.sampled_from([1, 2, 3, 4, 7, 8, 16, 19]), tau=st.integers(1, 5), d=st.integers(0, 6),
        xi=st.sampled_from([0.0, 0.125, 0.25, 0.6, 1.0]),
        sizes=st.lists(st.one_of(st.integers(1, 300), st.integers(4000, 9000)), min_size=1, max_size=4),
