@@ -62,10 +62,10 @@ class Bench:
         self.side = torch.cuda.Stream(dev)
         W, P = cfg.W, cfg.P
         off, n = cfg.params.offsets, cfg.params.n_tensors
-        ld = (P + 255) // 256 * 256          # row stride: rows 1 KiB aligned to each other
         with torch.cuda.stream(self.main):
             w0 = wl.init_weights(cfg, dev)
-            self._full = [torch.zeros(W, ld, device=dev) for _ in range(3)]
+            # W x ld matrices, rows 1 KiB aligned to each other: the layout of the arithmetic-addressed kernels
+            self._full = [pkg.DaSGD.replica_matrix(W, cfg.params.numel, dev)[0] for _ in range(3)]
             self.x, self.v, self.g = (a[:, :P] for a in self._full)
             self.x.copy_(w0.unsqueeze(0).expand(W, P))
             if cfg.kind == "external":

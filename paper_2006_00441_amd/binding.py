@@ -323,6 +323,26 @@ class DaSGD:
         return ws
 
     @staticmethod
+    def replica_matrix(W: int, numel: Sequence[int], device="cuda:0", row_align: int = 256):
+        """Storage in the layout the arithmetic-addressed kernels take (see dasgd_local_step): one
+        zero-filled W x ld fp32 matrix, ld = sum(numel) rounded up to row_align floats (256 floats =
+        1 KiB; the library accepts up to 255 floats of padding per row), and the per-tensor views
+        views[j][t] into row j.  Allocate one for the weights, one for the momentum buffers and one for
+        the gradients; the views are what a model uses as its parameters / gradient buffers.
+        Returns (matrix, views)."""
+        import torch
+        if row_align < 4 or row_align > 256 or row_align % 4:
+            raise ValueError("row_align must be a multiple of 4 floats, at most 256")
+        P = int(sum(int(n) for n in numel))
+        ld = (P + row_align - 1) // row_align * row_align
+        m = torch.zeros(int(W), ld, dtype=torch.float32, device=device)
+        off = [0]
+        for n in numel:
+            off.append(off[-1] + int(n))
+        views = [[m[j, off[t]:off[t + 1]] for t in range(len(numel))] for j in range(int(W))]
+        return m, views
+
+    @staticmethod
     def grad_pointers(g: Sequence[Sequence["torch.Tensor"]]):
         """The gradient table of local_step/step, marshalled once: W*n_tensors device pointers,
         replica-major, as a C array that can be passed at every step without being rebuilt."""

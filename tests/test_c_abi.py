@@ -209,3 +209,17 @@ def test_block_map_of_the_column_aware_kernels_covers_every_block_once():
     for bad in ((0, 64, 0), (8, 63, 0), (8, 2**28, 0), (8, 1000, 12), (8, 1000, -1)):
         with pytest.raises(DasgdError):
             pkg.check_block_map(*bad)
+
+
+def test_replica_matrix_helper_lays_rows_out_as_documented():
+    import torch
+    m, views = DaSGD.replica_matrix(3, [5, 300, 7], device="cpu")
+    assert m.shape == (3, 512) and m.dtype == torch.float32 and float(m.abs().sum()) == 0.0
+    assert [v.numel() for v in views[2]] == [5, 300, 7]
+    base = m.data_ptr()
+    assert views[0][0].data_ptr() == base and views[0][1].data_ptr() == base + 4 * 5
+    assert views[2][2].data_ptr() == base + 4 * (2 * 512 + 305)
+    assert DaSGD.replica_matrix(2, [256], device="cpu")[0].shape == (2, 256)
+    assert DaSGD.replica_matrix(2, [10], device="cpu", row_align=4)[0].shape == (2, 12)
+    with pytest.raises(ValueError):
+        DaSGD.replica_matrix(2, [10], device="cpu", row_align=512)
