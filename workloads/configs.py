@@ -1,4 +1,4 @@
-"""The benchmark configurations (the five workloads of this build's baseline file) as records.
+"""The five benchmark workloads as records.
 
 Each record fixes the parameter set, the number of replicas W (the paper's M, Section 3.3.1),
 the averaging period tau, the delay d, the optimiser constants and the step count.
