@@ -17,9 +17,10 @@
  *   - All pointers named "device" point to GPU memory owned by the CALLER (allocated e.g. by
  *     PyTorch); the library allocates no device memory.  All pointer ARRAYS are host memory.
  *   - Streams are raw hipStream_t handles passed as void*; the caller owns them.
- *   - Every step call only enqueues work and returns; only dasgd_bind (set-up copies),
- *     dasgd_profile_read and dasgd_destroy block the host (and dasgd_local_step when the gradient
- *     pointer table has changed four times while the GPU still works on the oldest of them).
+ *   - Every step call only enqueues work and returns; only dasgd_bind (set-up copies) and
+ *     dasgd_destroy block the host (and dasgd_local_step when the gradient pointer table has changed
+ *     four times while the GPU still works on the oldest of them).
+ *   - The library touches no byte outside the tensors, gradient buffers and workspace it is given.
  *   - A context is not thread-safe.  Functions return DASGD_OK or a negative error code and
  *     leave the context unchanged on error.
  *   - k denotes the 0-based index of the most recently completed local step.
@@ -29,6 +30,15 @@
  *     dasgd_query(ctx, &k, &n_pending, &begin_due, &merge_due);
  *     if (begin_due) dasgd_average_begin(ctx);     // (k+1) mod tau == 0
  *     if (merge_due) dasgd_merge(ctx);             // an average launched at k-d is pending
+ *
+ * Accuracy.  Results agree with a double-precision evaluation of Eq. 2 to within 1e-5 of the weight
+ * scale (per tensor: the larger of the rms of the weights and of their initial values) over runs of up
+ * to 3000 steps with the default settings.  Single-precision rounding accumulates like the square root
+ * of the step count (about 1.3e-7 sqrt(K) measured), so no fp32 implementation holds that bound much
+ * beyond 5000 steps; see DASGD_SNAPSHOT_* for the one setting that spends part of this budget.
+ *
+ * Diagnostics, tuning knobs and test hooks (profiling, band lengths, layout inspection, dry runs) are
+ * declared in dasgd_diag.h.
  */
 #ifndef DASGD_H
 #define DASGD_H
@@ -53,7 +63,7 @@ enum {
 
 /* Schedules (dasgd_set_schedule).  All use the same kernels. */
 enum {
-    DASGD_SCHED_OVERLAP = 0, /* default: the W-way mean runs on the side stream, event-ordered, beside
+    DASGD_SCHED_OVERLAP = 0, /* the W-way mean runs on the side stream, event-ordered, beside
                                 whatever the caller enqueues on the main stream after this step's calls
                                 (the next forward/backward pass -- the paper's point: averaging hidden
                                 behind local work, Fig. 2 and Fig. 4).  The library's own kernels, which
@@ -61,9 +71,23 @@ enum {
     DASGD_SCHED_SERIAL  = 1, /* everything on the main stream in program order (no overlap) */
     DASGD_SCHED_NO_AVERAGE_TIMING_ONLY = 2, /* timing floor: no snapshot and no mean are run, the
                                 merge reads whatever the slot holds.  RESULTS ARE MEANINGLESS. */
-    DASGD_SCHED_OVERLAP_FREE = 3 /* side-stream mean with the full d local steps of slack: main-stream
+    DASGD_SCHED_OVERLAP_FREE = 3, /* side-stream mean with the full d local steps of slack: main-stream
                                 kernels wait only for the average they read, so a mean may also run
                                 beside the library's own local steps and merges */
+    DASGD_SCHED_AUTO = 4     /* default: OVERLAP or SERIAL, whichever is faster in the caller's own loop.
+                                Whether the side stream pays depends on what runs between two steps:
+                                behind work that leaves wave slots free the mean disappears; beside
+                                nothing, or beside a kernel that fills every SIMD (one large GEMM), the
+                                two cross-stream hand-overs per step only cost time (measured on MI355X:
+                                1-2 % of the step).  After a warm-up of 16 steps (rounded to whole
+                                averaging periods, like the phases) the library alternates the two
+                                schedules in six phases of 8 steps, marks the phase boundaries with
+                                events on main_stream -- so the caller's own work is inside the
+                                measurement -- and keeps the schedule with the smaller total once the
+                                marks have completed (seen by a non-blocking query at a later step).
+                                Results do not depend on the choice.  A caller that captures the step
+                                calls into a HIP graph sets a fixed schedule first (event queries are
+                                illegal while capturing) */
 };
 
 /* How much of one iteration is fused into the local-step kernel (dasgd_set_fusion).  Results are the
@@ -78,9 +102,10 @@ enum {
                                   dasgd_merge only retires the average; otherwise as DASGD_FUSE_SNAPSHOT */
     DASGD_FUSE_ALL        = 3  /* the mean is computed by the local-step kernel too (a workgroup updates a
                                   window of columns of all W replicas and sums the new values through
-                                  LDS): no snapshot, no mean kernel, nothing on the side stream; dasgd_average_begin and dasgd_merge only keep the books.
-                                  What one GPU can do when the average need not be a separate,
-                                  overlappable operation.  Needs the W x P matrix layout and d > 0;
+                                  LDS): no snapshot, no mean kernel, nothing on the side stream;
+                                  dasgd_average_begin and dasgd_merge only keep the books.  What one GPU
+                                  can do when the average need not be a separate, overlappable operation.
+                                  Needs the rows layout (see dasgd_local_step) for x, v and g, and d > 0;
                                   otherwise behaves as DASGD_FUSE_STEP_MERGE */
 };
 
@@ -88,23 +113,30 @@ enum {
 enum {
     DASGD_SNAPSHOT_COPY      = 0, /* the local-step kernel stores them into a snapshot buffer (an extra
                                      4 bytes per element); the mean may then take its full d steps */
-    DASGD_SNAPSHOT_ZERO_COPY = 1  /* default: the live weights are the snapshot.  The mean reads x itself
-                                     and the next kernel that writes x waits for it.  On a step that also
-                                     merges an older average A (folded into the local step, so that x
-                                     already holds x' = xi y + (1 - xi) A), the mean of the y is recovered
-                                     as (mean x' - (1 - xi) A) / xi in double precision: same quantity,
-                                     rounding differs in the last bits (the fp32 rounding of the x' enters
-                                     amplified by 1/xi: measured against an fp64 run, about 1.6 times the
-                                     deviation of the copy mode, both growing like the square root of the
-                                     step count and below 1e-5 of the weight scale up to 3000 steps at
-                                     xi = 0.25).  The library's own kernels wait; a caller whose OWN kernels
-                                     write x between two steps (clipping, loading a checkpoint) must first
-                                     wait for side_stream, or use the copy mode.  Used when: matrix layout;
-                                     schedule OVERLAP or SERIAL; fusion level 2; and either no merge falls
-                                     on the step or xi >= 1/8.  Otherwise the copy is made. */
+    DASGD_SNAPSHOT_ZERO_COPY = 1, /* the live weights are the snapshot.  The mean reads x itself and the
+                                     next kernel that writes x waits for it.  On a step that also merges
+                                     an older average A (folded into the local step, so that x already
+                                     holds x' = xi y + (1 - xi) A), the mean of the y is recovered as
+                                     (mean x' - (1 - xi) A) / xi: same quantity, but the fp32 rounding of
+                                     the x' enters it amplified by 1/xi.  RUN-LENGTH LIMIT: measured
+                                     against a double-precision run the deviation grows like 2.2e-7
+                                     sqrt(K) of the weight scale at xi = 0.25 (1.3e-7 sqrt(K) with stored
+                                     snapshots) and reaches 1e-5 near K = 2000 steps; the extra term
+                                     scales with 1/xi.  The library's own kernels wait for the mean; a
+                                     caller whose OWN kernels write x between two steps (clipping,
+                                     loading a checkpoint) must first wait for side_stream, or use the
+                                     copy mode.  Taken when: every replica is one contiguous run (see
+                                     dasgd_local_step); schedule OVERLAP, SERIAL or AUTO; fusion level 2;
+                                     and either no merge falls on the step or xi >= 1/8.  Otherwise the
+                                     copy is made */
+    DASGD_SNAPSHOT_AUTO      = 2  /* default: zero-copy for the first 500 min(1, (xi / 0.25)^2) steps of
+                                     the context (none for xi < 1/8), stored snapshots from then on, so
+                                     that the accuracy statement at the top of this file holds whatever
+                                     the run length: the reconstruction's extra rounding is spent while
+                                     the accumulated error is still small */
 };
 
-/* Kernels for dasgd_profile_read. */
+/* Kernel kinds, for dasgd_profile_read and dasgd_band (dasgd_diag.h). */
 enum {
     DASGD_K_LOCAL_STEP         = 0, /* local step storing x, v                      (20 B per element) */
     DASGD_K_LOCAL_STEP_SNAP    = 1, /* local step storing x, v and the snapshot     (24 B per element) */
@@ -141,13 +173,6 @@ int dasgd_set_lr(dasgd_ctx *ctx, float lr);
 /* Choose the schedule (DASGD_SCHED_*).  Only legal while no average is pending. */
 int dasgd_set_schedule(dasgd_ctx *ctx, int schedule);
 
-/* In the overlap schedules a mean that reads and writes fewer than `bytes` bytes ((W+1) rows of fp32)
- * is launched on main_stream after all: handing work to the side stream and back costs two
- * cross-stream waits of 6-10 us each on MI355X, more than so small a mean takes (at 6 TB/s, 64 MiB are
- * 11 us).  Default 64 MiB; 0 sends every mean to the side stream.  Results do not depend on it.
- * ESTATE while averages are pending or an average is due. */
-int dasgd_set_side_stream_threshold(dasgd_ctx *ctx, size_t bytes);
-
 /* Choose the fusion level (DASGD_FUSE_*).  Only legal while no average is pending. */
 int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
 
@@ -155,10 +180,10 @@ int dasgd_set_fusion(dasgd_ctx *ctx, int fusion);
 int dasgd_set_snapshot(dasgd_ctx *ctx, int mode);
 
 /* Bytes of device workspace dasgd_bind needs for a model of n_tensors tensors with numel[t]
- * elements each (sum must equal P).  Holds the chunk and pointer tables, the snapshots
+ * elements each (sum must equal P).  Holds the record and pointer tables, the snapshots
  * (floor(d/tau)+1 slots of W x P' floats) and the averages (same number of slots of P' floats),
- * where P' pads every tensor to a multiple of 64 elements and adds 256.  Returns 0 on invalid
- * arguments. */
+ * where P' pads every tensor to a multiple of 64 elements, rounds up to 256 and adds 256.  Returns 0
+ * on invalid arguments (also: a tensor of 2^32 elements or more, P' of 2^32 or more). */
 size_t dasgd_workspace_bytes(const dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
 
 /* Bind the replicas' storage.
@@ -185,11 +210,6 @@ int dasgd_bind(dasgd_ctx *ctx, int n_tensors, const int64_t *numel,
                void *workspace, size_t workspace_bytes,
                void *main_stream, void *side_stream);
 
-/* Bind shapes only: every later step call runs the host-side state machine (step counter,
- * pending-average ring, due/overdue checks, error codes) and launches NOTHING on any device.
- * For testing schedules and error handling on machines without a GPU; computes nothing. */
-int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
-
 /* Local step k -> k+1 on every replica (Eq. 2, first branch, with the optimiser of Section 4.1):
  *     g' = g + wd x ;  v <- momentum v + g' ;  x <- x - lr v
  * one fused kernel over all replicas and tensors on main_stream.  What else that kernel does depends
@@ -205,13 +225,17 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  *       pointers of the previous call (the table is re-uploaded only when it changes; four device
  *       copies are used in rotation, so a caller that changes it at every step can run at most three
  *       changes ahead of the GPU before this call waits).
- * Layout: if x and v (and g) are W x P row-major matrices -- every replica's tensors back to back
- * in the order given, one common row stride ld with P <= ld < P + 256 floats and ld a multiple of 4,
- * base 16-byte aligned -- the kernels address them by arithmetic alone (fastest; fastest of all when
- * ld is a multiple of 32, so that rows are 128-byte aligned to each other).  The up to 255 floats
- * behind every row, the last one included, are then padding that BELONGS TO THE MATRIX: the library
- * reads and overwrites them (if the allocation ends before the last row's padding does, the layout is
- * not taken for a matrix).  Any other layout goes through a chunk table.  Results are identical.
+ * Layout.  Rows: when every replica's tensors lie back to back in the order given, so that replica j
+ * is ONE contiguous run of P floats starting at a 16-byte aligned address -- the rows of a W x ld
+ * matrix with any row stride ld >= P, or one arena per replica at any addresses -- and P is a multiple of
+ * 4 and W <= 32, the kernels take the W row addresses of x, v and g as arguments and need no table in
+ * memory (fastest; a little faster still when the rows start on 1 KiB boundaries of the same phase for
+ * x, v and g).  Only the P floats of each row are touched: padding between rows stays the caller's.
+ * Records: any other arrangement (one allocation per tensor, odd sizes, unaligned tensors, W > 32) goes
+ * through a table with one record per replica and 4096-float piece of a tensor; 128-bit accesses where
+ * the piece's addresses are 16-byte aligned, 32-bit accesses otherwise.  x and v select the addressing
+ * at dasgd_bind, g whenever its table changes (rows for x and v with any g is fine).  Results are
+ * identical, bit for bit.
  * A changed gradient table is checked against its allocations like the tensors at dasgd_bind, and
  * against x, v and the workspace for shared bytes (EINVAL); gradient buffers may alias each other.
  * ESTATE: not bound; an average or a merge that fell due at the previous step was not issued. */
@@ -245,6 +269,7 @@ int dasgd_step(dasgd_ctx *ctx, const float *const *g, int *began, int *merged);
  * per-worker form, x_{k+1} = x_k - (eta/M) sum_j g_j (Section 2.1, Eq. 1), provided so that the
  * paper's comparison schedules (Mini-batch SGD, Local SGD as d = 0) can be timed on the same kernels.
  *   G    device, W*P floats, rows back to back, 16-byte aligned, read only;  P must be a multiple of 4
+ *        (the sum is taken pairwise over the replicas for W <= 32, four rows at a time above)
  *   out  device, P floats, 16-byte aligned; may then be passed as every replica's gradient
  * EINVAL: null / misaligned pointer or P % 4 != 0.  ESTATE: not bound. */
 int dasgd_gradient_average(dasgd_ctx *ctx, const float *G, float *out);
@@ -259,69 +284,6 @@ int dasgd_choose_delay(double t_c, double t_p, int *d, int *tau);
  * pending averages, and whether dasgd_average_begin / dasgd_merge are due now.  Any output
  * pointer may be NULL. */
 int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begin_due, int *merge_due);
-
-/* Layout of the library-owned buffers inside the workspace, for inspection by tests and tools:
- * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
- * *P_padded = elements per row: the row stride ld when x and v were bound as W x P matrices (rows
- * mirror that layout), otherwise every tensor padded to a multiple of 64 elements (plus 256).
- * ESTATE if not bound. */
-int dasgd_layout(const dasgd_ctx *ctx, int64_t *flat_offset, int64_t *P_padded);
-
-/* Locate pending average number `which` (0 = oldest): its launch step and the byte offset of its
- * P_padded floats from the start of the workspace.  The data is complete once side_stream (or
- * main_stream in the serial schedule) has drained.  EINVAL if which is out of range. */
-int dasgd_pending_average(const dasgd_ctx *ctx, int which, int64_t *launch_step, size_t *byte_offset);
-
-/* Per-kernel timing.  every_n >= 1: bracket one launch in every_n of each kernel kind with timing
- * events on its own stream (at most max_records launches are recorded; later ones run untimed);
- * every_n == 0: stop.  An event pair costs a few microseconds on the stream, hence the sampling. */
-int dasgd_profile(dasgd_ctx *ctx, int every_n, int max_records);
-
-/* Wait for both streams, then return, for kernel `kernel` (DASGD_K_*) since profiling was enabled
- * or last read: the summed duration of the timed launches, how many were timed, and how many were
- * launched in all; then reset the three.  Any output pointer may be NULL. */
-int dasgd_profile_read(dasgd_ctx *ctx, int kernel, double *total_ms, int64_t *timed, int64_t *launched);
-
-/* Work order of the matrix-layout kernels that read the average (folded local step, merge).  Their
- * workgroups walk the W x P matrix in bands: 2^log_band column windows (1 KiB each, per L2 partition)
- * of replica 0, the same windows of replica 1, ..., then the next band, so that a band's piece of the
- * average is read from HBM once and from the L2 afterwards.  Which band length is fastest depends on P,
- * W and on what runs around the kernel (measured on MI355X: up to 8 % between lengths, with a
- * different winner for each benchmark shape), so by default the library measures it in place: the
- * first 16 launches of such a kernel rotate through five lengths, three launches of each bracketed
- * by timing events on main_stream; finished events are collected without waiting at later launches,
- * and the fastest length is kept from then on.  The order never changes results: every element is
- * computed by the same arithmetic whichever workgroup handles it (bit-identical, tested).  The
- * chunk-table kernel (other layouts) has two orders for a folded merge -- replica after replica, or
- * the W replicas of a chunk back to back on one L2 partition -- and is measured the same way; a fixed
- * log_band selects the second.
- *   log_band  -1: measure (default);  0..11: use this length (clamped to the row length).
- * May be called at any time.  EINVAL outside -1..11.  A caller that captures the step calls into a HIP
- * graph fixes the length first (the measurement queries events, which a capturing stream forbids) --
- * for instance to the value dasgd_band reported after a few eager steps. */
-int dasgd_set_band(dasgd_ctx *ctx, int log_band);
-
-/* Band length in use for kernel `kernel` (DASGD_K_STEP_MERGE, DASGD_K_STEP_SNAP_MERGE or DASGD_K_MERGE):
- * *log_band = the fixed or measured value, -1 while the measurement is still running; *settled = 1
- * once it is final; *trials = timed trial launches issued so far for this kernel (0: it has not run
- * more than once yet).  Looks at finished timing events but never waits.  Any output pointer may be
- * NULL.  ESTATE if not bound. */
-int dasgd_band(dasgd_ctx *ctx, int kernel, int *log_band, int *settled, int *trials);
-
-/* The extent check of dasgd_bind, for callers and tests: *bytes_to_end = number of bytes from p to the
- * end of the device allocation that holds it, as the HIP runtime knows it (a framework's caching
- * allocator may have carved p out of a larger allocation: the figure is an upper bound on what belongs
- * to the caller).  EINVAL if p is NULL or not inside an allocation the runtime knows. */
-int dasgd_device_extent(const void *p, size_t *bytes_to_end);
-
-/* Host-only self-check of the index arithmetic behind that work order, with the very function the
- * kernels use: for a W x (4*row4)-float matrix and band length 2^log_band (clamped as the library
- * would), every aligned 64-column block of the flat index space must be handled by exactly one
- * workgroup, on behalf of the row that holds its first element, and no workgroup may point past the
- * end.  Returns 0 if so, 1..4 naming the violated property (start past the end, wrong row, handled
- * twice, never handled); EINVAL for sizes outside what those kernels accept (row4 < 64, W*row4 + 64
- * >= 2^31, log_band outside 0..11). */
-int dasgd_check_block_map(int W, int64_t row4, int log_band);
 
 /* HIP error code of the most recent DASGD_EHIP (0 if none). */
 int dasgd_last_hip_error(const dasgd_ctx *ctx);

@@ -1,4 +1,4 @@
-"""ctypes binding of include/dasgd.h: argument marshalling only.
+"""ctypes binding of include/dasgd.h and include/dasgd_diag.h: argument marshalling only.
 
 `lib()` returns the loaded shared library with typed signatures; `DaSGD` wraps one context and
 turns negative return codes into `DasgdError`.  Every method maps one-to-one onto the C call of
@@ -15,10 +15,12 @@ from typing import List, Optional, Sequence, Tuple
 from . import build as _build
 
 DASGD_OK, DASGD_EINVAL, DASGD_ESTATE, DASGD_ENOMEM, DASGD_EHIP = 0, -1, -2, -3, -4
-SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY, SCHED_OVERLAP_FREE = 0, 1, 2, 3
+SCHED_OVERLAP, SCHED_SERIAL, SCHED_NO_AVERAGE_TIMING_ONLY, SCHED_OVERLAP_FREE, SCHED_AUTO = 0, 1, 2, 3, 4
 K_LOCAL_STEP, K_LOCAL_STEP_SNAP, K_MEAN, K_MERGE, K_LOCAL_STEP_TO_SNAP, K_STEP_MERGE, K_STEP_SNAP_MERGE = 0, 1, 2, 3, 4, 5, 6
 K_STEP_MEAN, K_STEP_MEAN_MERGE, K_MEAN_RECONSTRUCT = 7, 8, 9
-SNAPSHOT_COPY, SNAPSHOT_ZERO_COPY = 0, 1
+SNAPSHOT_COPY, SNAPSHOT_ZERO_COPY, SNAPSHOT_AUTO = 0, 1, 2
+ADDR_RECORDS, ADDR_ROWS, ADDR_ROWS_XV = 0, 1, 2
+MAP_ROWS, MAP_MEAN, MAP_MEAN_RUNS = 0, 1, 2
 FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE, FUSE_ALL = 0, 1, 2, 3
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
                 K_MEAN: "mean", K_MERGE: "merge", K_LOCAL_STEP_TO_SNAP: "local_step_to_snapshot",
@@ -34,7 +36,7 @@ _pp = ctypes.POINTER(ctypes.c_void_p)
 _pi64 = ctypes.POINTER(ctypes.c_int64)
 _pint = ctypes.POINTER(ctypes.c_int)
 
-# name -> (restype, argtypes): every symbol include/dasgd.h declares
+# name -> (restype, argtypes): every symbol include/dasgd.h and include/dasgd_diag.h declare
 EXPORTS = {
     "dasgd_create": (_vp, [ctypes.c_int, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_float]),
     "dasgd_set_xi": (ctypes.c_int, [_vp, ctypes.c_float]),
@@ -53,14 +55,15 @@ EXPORTS = {
     "dasgd_gradient_average": (ctypes.c_int, [_vp, _vp, _vp]),
     "dasgd_choose_delay": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, _pint, _pint]),
     "dasgd_query": (ctypes.c_int, [_vp, _pi64, _pint, _pint, _pint]),
-    "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64]),
+    "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64, _pint]),
     "dasgd_pending_average": (ctypes.c_int, [_vp, ctypes.c_int, _pi64, ctypes.POINTER(ctypes.c_size_t)]),
     "dasgd_profile": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
     "dasgd_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _pi64, _pi64]),
     "dasgd_set_band": (ctypes.c_int, [_vp, ctypes.c_int]),
     "dasgd_band": (ctypes.c_int, [_vp, ctypes.c_int, _pint, _pint, _pint]),
     "dasgd_device_extent": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
-    "dasgd_check_block_map": (ctypes.c_int, [ctypes.c_int, _i64, ctypes.c_int]),
+    "dasgd_check_work_map": (ctypes.c_int, [ctypes.c_int, _i64, ctypes.c_int, ctypes.c_int]),
+    "dasgd_schedule_in_use": (ctypes.c_int, [_vp, _pint, _pint, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
 }
@@ -82,11 +85,19 @@ def library_path() -> str:
 
 
 def lib() -> ctypes.CDLL:
-    """Load libdasgd.so (what is built in-tree; built here only if nothing is)."""
+    """Load libdasgd.so (what is built in-tree; built here if nothing is, rebuilt if a source is newer
+    where a compiler is at hand -- a library older than its sources is never loaded silently)."""
     global _LIB
     if _LIB is not None:
         return _LIB
     path = library_path()
+    if os.path.exists(path) and _build.stale():
+        try:
+            _build.hipcc()
+        except RuntimeError:
+            raise RuntimeError("libdasgd.so is older than its sources and there is no hipcc here to rebuild it; "
+                               "run `python -c 'import __graft_entry__ as g; g.build()'` where there is one") from None
+        _build.build()
     if not os.path.exists(path):
         try:
             _build.build()
@@ -120,12 +131,12 @@ def device_extent(ptr: int) -> int:
     return int(n.value)
 
 
-def check_block_map(W: int, row4: int, log_band: int) -> int:
-    """0 if the work order of the column-aware kernels covers a W x 4*row4 matrix exactly once
-    (dasgd_check_block_map); 1..4 name the violated property; raises on sizes the kernels do not take."""
-    rc = lib().dasgd_check_block_map(int(W), int(row4), int(log_band))
+def check_work_map(kind: int, row4: int, head: int = 0, log_band: int = 0) -> int:
+    """0 if the work map `kind` (MAP_*) covers a row of row4 128-bit columns exactly once
+    (dasgd_check_work_map); 1..4 name the violated property; raises on arguments out of range."""
+    rc = lib().dasgd_check_work_map(int(kind), int(row4), int(head), int(log_band))
     if rc < 0:
-        raise DasgdError("dasgd_check_block_map", rc)
+        raise DasgdError("dasgd_check_work_map", rc)
     return rc
 
 
@@ -227,8 +238,21 @@ class DaSGD:
         """(flat offset of every tensor in a snapshot row / average, padded row length)"""
         off = (ctypes.c_int64 * max(self.n_tensors, 1))()
         pp = ctypes.c_int64()
-        self._check("dasgd_layout", self._lib.dasgd_layout(self._h, off, ctypes.byref(pp)))
+        self._check("dasgd_layout", self._lib.dasgd_layout(self._h, off, ctypes.byref(pp), None))
         return [int(o) for o in off[: self.n_tensors]], int(pp.value)
+
+    def addressing(self) -> int:
+        """ADDR_RECORDS, ADDR_ROWS or ADDR_ROWS_XV (-1 for a dry run): how the kernels find the data."""
+        a = ctypes.c_int()
+        self._check("dasgd_layout", self._lib.dasgd_layout(self._h, None, None, ctypes.byref(a)))
+        return int(a.value)
+
+    def schedule_in_use(self) -> Tuple[int, bool, float, float]:
+        """(schedule in force -- SCHED_AUTO while still measuring --, settled?, overlap ms, serial ms)"""
+        sc = ctypes.c_int(); st = ctypes.c_int(); a = ctypes.c_double(); b = ctypes.c_double()
+        self._check("dasgd_schedule_in_use", self._lib.dasgd_schedule_in_use(self._h, ctypes.byref(sc), ctypes.byref(st),
+                                                                             ctypes.byref(a), ctypes.byref(b)))
+        return int(sc.value), bool(st.value), float(a.value), float(b.value)
 
     def pending_average(self, which: int = 0) -> Tuple[int, int]:
         """(launch step, byte offset into the workspace) of pending average `which` (0 = oldest)"""
@@ -324,15 +348,15 @@ class DaSGD:
 
     @staticmethod
     def replica_matrix(W: int, numel: Sequence[int], device="cuda:0", row_align: int = 256):
-        """Storage in the layout the arithmetic-addressed kernels take (see dasgd_local_step): one
-        zero-filled W x ld fp32 matrix, ld = sum(numel) rounded up to row_align floats (256 floats =
-        1 KiB; the library accepts up to 255 floats of padding per row), and the per-tensor views
+        """Storage in the layout the row kernels take (see dasgd_local_step): one zero-filled W x ld
+        fp32 matrix, ld = sum(numel) rounded up to row_align floats (256 floats = 1 KiB: rows that start
+        on kilobyte boundaries are the fastest; any stride works), and the per-tensor views
         views[j][t] into row j.  Allocate one for the weights, one for the momentum buffers and one for
         the gradients; the views are what a model uses as its parameters / gradient buffers.
         Returns (matrix, views)."""
         import torch
-        if row_align < 4 or row_align > 256 or row_align % 4:
-            raise ValueError("row_align must be a multiple of 4 floats, at most 256")
+        if row_align < 4 or row_align > 4096 or row_align % 4:
+            raise ValueError("row_align must be a multiple of 4 floats, at most 4096")
         P = int(sum(int(n) for n in numel))
         ld = (P + row_align - 1) // row_align * row_align
         m = torch.zeros(int(W), ld, dtype=torch.float32, device=device)

@@ -10,7 +10,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdasgd.so")
 SOURCES = [os.path.join(CSRC, "dasgd.hip")]
-DEPENDS = SOURCES + [os.path.join(CSRC, "kernels.hpp"), os.path.join(ROOT, "include", "dasgd.h")]
+DEPENDS = SOURCES + [os.path.join(CSRC, "kernels.hpp"), os.path.join(ROOT, "include", "dasgd.h"),
+                     os.path.join(ROOT, "include", "dasgd_diag.h")]
+STUDY = os.path.join(HERE, "shape_study")            # stand-alone launch-shape study (see csrc/shape_study.hip)
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",    # keep the compiler off packed-fp32 forms
@@ -38,6 +40,15 @@ def build(force: bool = True, extra_flags=(), out: str = LIB) -> str:
     tmp = out + f".tmp{os.getpid()}"
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-o", tmp, *SOURCES]
     subprocess.run(cmd, check=True)
+    os.replace(tmp, out)
+    return out
+
+
+def build_study(out: str = STUDY) -> str:
+    """The stand-alone launch-shape study program (an executable; it times kernel variants on the GPU)."""
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    tmp = out + f".tmp{os.getpid()}"
+    subprocess.run([hipcc(), *flags, "-o", tmp, os.path.join(CSRC, "shape_study.hip")], check=True)
     os.replace(tmp, out)
     return out
 

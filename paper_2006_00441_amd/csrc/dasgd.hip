@@ -1,8 +1,9 @@
-// Host side of the DaSGD parameter pipeline: the C ABI declared in include/dasgd.h, the
-// pending-average ring, and the stream/event schedule that lets the W-way mean run behind the
-// following local steps (paper, Section 3 and Fig. 2: a worker hands its weights to the averaging
-// and immediately continues; the result is applied d local steps later).
+// Host side of the DaSGD parameter pipeline: the C ABI declared in include/dasgd.h and
+// include/dasgd_diag.h, the pending-average ring, and the stream/event schedule that lets the W-way
+// mean run behind the following local steps (paper, Section 3 and Fig. 2: a worker hands its weights to
+// the averaging and immediately continues; the result is applied d local steps later).
 #include "../../include/dasgd.h"
+#include "../../include/dasgd_diag.h"
 #include "kernels.hpp"
 
 #include <cmath>
@@ -20,13 +21,15 @@ namespace {
 
 constexpr int kGTables = 4;         // device copies of the gradient pointer table, used in rotation
 constexpr size_t kAlign = 256;
+constexpr int64_t kRowAlign = 256;  // library-owned rows start on 1 KiB boundaries
 
 inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 struct Pending {
     int64_t launch_step;
     int slot;
-    bool awaited;       // the main stream already waits for this average's mean kernel
+    bool on_side;       // its mean kernel was launched on the side stream
+    bool awaited;       // the main stream already waits for it (or it ran there)
 };
 
 struct ProfRec {
@@ -34,15 +37,15 @@ struct ProfRec {
     hipEvent_t start, stop;
 };
 
-// Which band length (see decode_block) is fastest depends on the row length and on what runs around
-// the kernel, so it is measured where it matters: in the caller's own steps.  The first launches of
-// a kernel kind rotate through the candidates, a few of them bracketed by timing events; finished
-// events are collected with non-blocking queries at later launches (the host never waits), and once
-// every candidate has its samples the fastest is kept.  The band length only permutes which
-// workgroup handles which block: results are bit-identical for every choice.
+// Which band length (see the three-dimensional grids in kernels.hpp) is fastest depends on the row
+// length and on what runs around the kernel, so it is measured where it matters: in the caller's own
+// steps.  The first launches of a kernel kind rotate through the candidates, a few of them bracketed by
+// timing events; finished events are collected with non-blocking queries at later launches (the host
+// never waits), and once every candidate has its samples the fastest is kept.  The band length only
+// permutes which workgroup handles which block: results are bit-identical for every choice.
 struct BandTuner {
     static constexpr int kMaxCand = 5, kSamples = 3;
-    int cand[kMaxCand] = {0, 8, 9, 10, 11};     // log2 of the band length
+    int cand[kMaxCand] = {5, 8, 9, 10, 11};     // log2 of the band length
     int n_cand = 0;                             // 0: candidates not yet fitted to the row length
     double sum_ms[kMaxCand] = {};
     int done[kMaxCand] = {}, issued[kMaxCand] = {};
@@ -53,11 +56,27 @@ struct BandTuner {
     std::vector<hipEvent_t> spare;
 };
 
+// Whether the side stream pays depends on what the caller runs between two steps: beside work that
+// leaves wave slots free the mean disappears behind it; beside nothing, or beside a kernel that fills
+// every SIMD, the two cross-stream hand-overs only cost time.  DASGD_SCHED_AUTO therefore measures:
+// after a warm-up phase the schedule alternates between OVERLAP and SERIAL in phases of a few steps, an
+// event on the main stream marks every phase boundary (so the caller's own work is inside the
+// measurement), and once all events have completed -- seen by a non-blocking query at a later step --
+// the schedule with the smaller total is kept.
+struct ScheduleTuner {
+    static constexpr int kPhases = 7;           // phase 0 is the warm-up; 1, 3, 5 OVERLAP; 2, 4, 6 SERIAL
+    int phase = 0, steps_in_phase = 0, phase_len = 8;
+    int chosen = -1;                            // DASGD_SCHED_OVERLAP or DASGD_SCHED_SERIAL once decided
+    hipEvent_t ev[kPhases + 1] = {};
+    int n_ev = 0;
+    double overlap_ms = 0, serial_ms = 0;
+};
+
 struct Layout {                     // byte offsets into the workspace
-    size_t chunks, xp, vp, gp[kGTables], S, A, total;
-    int64_t P_pad, n_chunks;        // P_pad: elements per snapshot row / average
+    size_t recs, gp[kGTables], S, A, total;
+    int64_t P_pad, n_pieces;        // P_pad: floats per snapshot row / average
     std::vector<int64_t> foff;      // start of each tensor inside such a row
-    bool flat = false;              // rows mirror the caller's matrix (foff = plain prefix sums, P_pad = row stride)
+    bool rows = false;              // rows mirror the replicas' own layout (foff = plain prefix sums)
 };
 
 }  // namespace
@@ -67,9 +86,9 @@ struct dasgd_ctx {
     int W = 0, d = 0, tau = 1;
     int64_t P = 0;
     float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
-    int schedule = DASGD_SCHED_OVERLAP;
+    int schedule = DASGD_SCHED_AUTO;
     int fusion = DASGD_FUSE_STEP_MERGE;
-    int snapshot = DASGD_SNAPSHOT_ZERO_COPY;
+    int snapshot = DASGD_SNAPSHOT_AUTO;
     int slots = 1;
     size_t side_min_bytes = (size_t)64 << 20;   // means that move less than this run on the main stream
     // binding
@@ -79,6 +98,10 @@ struct dasgd_ctx {
     Layout lay;
     char *ws = nullptr;
     hipStream_t main_s = nullptr, side_s = nullptr;
+    // rows addressing: every replica's tensors are one contiguous, 16-byte aligned run of P floats
+    bool xv_rows = false, g_rows = false;
+    RowSet xr = {}, vr = {};
+    ConstRowSet gr = {};
     // gradient pointer tables
     std::vector<const float *> g_cached;
     std::vector<std::pair<uintptr_t, size_t>> owned;    // byte ranges of x, v and the workspace, sorted by start
@@ -90,8 +113,8 @@ struct dasgd_ctx {
     int64_t n_done = 0;             // completed local steps; k = n_done - 1
     int64_t n_launched = 0;         // averages launched so far
     bool begun_for_k = false;       // dasgd_average_begin already issued for the current k
-    bool snap_valid = false;        // the latest local step stored a snapshot
-    bool y_in_snap = false;         // ... and ONLY the snapshot: x is stale until this step's merge
+    bool snap_valid = false;        // the latest local step prepared an average (snapshot stored, or zero-copy)
+    bool y_in_snap = false;         // ... and stored ONLY the snapshot: x is stale until this step's merge
     bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
     bool merged_in_step = false;    // the latest local step already applied this step's merge
     bool mean_in_step = false;      // ... and already computed the average that average_begin will register
@@ -100,17 +123,10 @@ struct dasgd_ctx {
     int zc_old_slot = 0;            // ... with the average in this slot
     float zc_xi = 0.25f;            // ... and this xi
     int snap_slot = 0;
-    // matrix layout: x, v (and g) are W x P row-major matrices with one row stride, 16-byte aligned
-    bool xv_matrix = false, g_matrix = false;
-    int64_t ld = 0;                 // row stride of that matrix in elements (P <= ld < P + 256)
-    float *x0 = nullptr, *v0 = nullptr;
-    const float *g0 = nullptr;
+    int sched_now = DASGD_SCHED_OVERLAP;   // the schedule in effect for the step being issued (fixed per step)
     int band_fixed = -1;            // >= 0: log2 of the band length set by the caller; -1: measured (BandTuner)
     BandTuner tuner[DASGD_K_COUNT];
-    BandTuner table_tuner[2];       // chunk-table local step with a folded merge (0: no snapshot store, 1: with):
-                                    // candidates -1 (replica-major grid) and 0 (replicas of a chunk on one XCD)
-    bool idx32 = false;             // 64 <= P/4 and W*P/4 + 64 < 2^31: the column-aware flat kernels apply
-                                    // (32-bit indices; a 64-element block spans at most two rows)
+    ScheduleTuner sched_tuner;
     std::deque<Pending> pending;
     std::vector<hipEvent_t> snap_done, avg_done;
     // profiling
@@ -138,69 +154,59 @@ bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
     if (!c || n_tensors < 1 || !numel) return false;
     int64_t sum = 0;
     for (int t = 0; t < n_tensors; ++t) {
-        if (numel[t] < 1) return false;
+        if (numel[t] < 1 || numel[t] >= (1ll << 32)) return false;
         sum += numel[t];
     }
     return sum == c->P;
 }
 
-// Rows of the library-owned buffers either pad every tensor to a 256-byte boundary (so the table
-// kernels can always use 128-bit accesses on them) or, when the caller's x and v are W x P matrices,
-// mirror that layout, row stride included (so one flat index addresses x, v, g and the snapshot
-// alike).  The byte offsets of the padded layout are used in both cases: the workspace size must not
-// depend on pointers that dasgd_workspace_bytes never sees.
-constexpr int64_t kMaxRowPad = 256;  // a matrix row may be followed by fewer than this many padding floats
-
-Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool flat = false, int64_t ld = 0)
+// Rows of the library-owned buffers (snapshots, averages) either pad every tensor to a 256-byte
+// boundary (so that the record kernels can use 128-bit accesses on them whatever the tensor sizes) or,
+// when every replica is one contiguous run, mirror that run (column c of a snapshot row is column c of
+// the replica).  The byte offsets of the padded layout are used in both cases: the workspace size must
+// not depend on pointers that dasgd_workspace_bytes never sees.
+Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool rows = false)
 {
     Layout L;
     L.foff.resize(n_tensors);
-    int64_t f = 0, fp = 0, nch = 0;
+    int64_t f = 0, fp = 0, np = 0;
     for (int t = 0; t < n_tensors; ++t) {
-        L.foff[t] = flat ? fp : f;
+        L.foff[t] = rows ? fp : f;
         fp += numel[t];
         f += (numel[t] + kPad - 1) / kPad * kPad;
-        nch += (numel[t] + kChunk - 1) / kChunk;
+        np += (numel[t] + kPiece - 1) / kPiece;
     }
-    L.flat = flat;
-    f += kMaxRowPad;                // room for the row padding of the matrix layout
+    L.rows = rows;
+    f = (f + kRowAlign - 1) / kRowAlign * kRowAlign + kRowAlign;
     L.P_pad = f;                    // sizes below always use the padded row length
-    L.n_chunks = nch;
+    L.n_pieces = np;
     const size_t tbl = sizeof(void *) * (size_t)c->W * (size_t)n_tensors;
     size_t o = 0;
-    L.chunks = o; o += align_up(sizeof(Chunk) * (size_t)nch);
-    L.xp = o;     o += align_up(tbl);
-    L.vp = o;     o += align_up(tbl);
+    L.recs = o;   o += align_up(sizeof(Rec) * (size_t)c->W * (size_t)np);
     for (int b = 0; b < kGTables; ++b) { L.gp[b] = o; o += align_up(tbl); }
     L.S = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)c->W * (size_t)L.P_pad);
     L.A = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)L.P_pad);
     L.total = o;
-    if (flat) L.P_pad = ld;
+    if (rows) L.P_pad = (c->P + kRowAlign - 1) / kRowAlign * kRowAlign;
     return L;
 }
 
-// True when ptr[j*n + t] == ptr[0] + j*ld + (unpadded offset of t) for all j, t with one row stride ld,
-// P <= ld < P + kMaxRowPad, ld a multiple of 4, base 16-byte aligned: a W x P row-major matrix whose
-// rows are back to back or separated by a little alignment padding (which then belongs to the matrix).
+// True when, for every replica j, ptr[j*n + t] == ptr[j*n] + (unpadded offset of t) and ptr[j*n] is
+// 16-byte aligned, with P a multiple of 4 below 2^33 and at most kMaxRows replicas: every replica is one
+// contiguous run of P floats (rows of a matrix with any stride, or one arena per replica).
 template <typename T>
-bool is_matrix(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr, int64_t *ld_out)
+bool is_rows(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr)
 {
-    if (reinterpret_cast<uintptr_t>(ptr[0]) & 15u) return false;
-    int64_t ld = c->P;
-    if (c->W > 1) {
-        const uintptr_t a = reinterpret_cast<uintptr_t>(ptr[0]), b = reinterpret_cast<uintptr_t>(ptr[n_tensors]);
-        if (b <= a || (b - a) % sizeof(float)) return false;
-        ld = (int64_t)((b - a) / sizeof(float));
-    }                               // (one row: nothing tells a stride, so ld = P)
-    if (ld < c->P || ld - c->P >= kMaxRowPad || ld % 4 != 0) return false;
+    if (c->W > kMaxRows || c->P % 4 != 0 || c->P / 4 > (1ll << 31) - 256) return false;
     for (int j = 0; j < c->W; ++j) {
+        T *base = ptr[(size_t)j * n_tensors];
+        if (reinterpret_cast<uintptr_t>(base) & 15u) return false;
         int64_t off = 0;
         for (int t = 0; t < n_tensors; ++t) {
-            if (ptr[(size_t)j * n_tensors + t] != ptr[0] + (int64_t)j * ld + off) return false;
+            if (ptr[(size_t)j * n_tensors + t] != base + off) return false;
             off += numel[t];
         }
     }
-    *ld_out = ld;
     return true;
 }
 
@@ -251,12 +257,23 @@ inline float *avg_ptr(const dasgd_ctx *c, int slot)
     return reinterpret_cast<float *>(c->ws + c->lay.A) + (size_t)slot * (size_t)c->lay.P_pad;
 }
 
+// The schedule in effect for the step being issued.
+inline int effective_schedule(const dasgd_ctx *c)
+{
+    if (c->schedule != DASGD_SCHED_AUTO) return c->schedule;
+    const ScheduleTuner &t = c->sched_tuner;
+    if (t.chosen >= 0) return t.chosen;
+    if (t.phase >= ScheduleTuner::kPhases) return DASGD_SCHED_OVERLAP;       // measured, result still to come
+    return (t.phase == 0 || (t.phase & 1)) ? DASGD_SCHED_OVERLAP : DASGD_SCHED_SERIAL;
+}
+
 // The mean goes to the side stream in the overlap schedules -- unless it is so small that the two
 // cross-stream hand-overs (main -> side before it, side -> main after it; 6-10 us each on MI355X)
 // cost more than running it in line could ever lose.
 inline bool side_stream_mean(const dasgd_ctx *c)
 {
-    if (c->schedule != DASGD_SCHED_OVERLAP && c->schedule != DASGD_SCHED_OVERLAP_FREE) return false;
+    const int s = c->sched_now;
+    if (s != DASGD_SCHED_OVERLAP && s != DASGD_SCHED_OVERLAP_FREE) return false;
     const size_t mean_bytes = sizeof(float) * (size_t)(c->W + 1) * (size_t)c->lay.P_pad;
     return mean_bytes >= c->side_min_bytes;
 }
@@ -268,6 +285,20 @@ inline bool begin_due(const dasgd_ctx *c)
 inline bool merge_due(const dasgd_ctx *c)
 {
     return !c->pending.empty() && c->pending.front().launch_step == (c->n_done - 1) - c->d;
+}
+
+// Steps for which DASGD_SNAPSHOT_AUTO takes the zero-copy path.  Measured against a double-precision run
+// (W = 8, tau = 1, d = 2, random gradients) the deviation of every fp32 implementation grows like the
+// square root of the step count K: about 1.3e-7 sqrt(K) of the weight scale with stored snapshots, and
+// 2.2e-7 sqrt(K) with the reconstruction at xi = 0.25, whose extra term scales with 1/xi.  The budget keeps
+// the reconstruction's share small enough that the whole run stays below 1e-5 for 3000 steps with a
+// quarter to spare (sqrt(500 * 2.2e-7^2 + 2500 * 1.3e-7^2) = 7.2e-6): 500 steps at xi >= 0.25, fewer in
+// proportion to xi^2 below, none below xi = 1/8.
+inline int64_t zero_copy_budget(float xi)
+{
+    if (xi < 0.125f) return 0;
+    const double r = std::min(1.0, (double)xi / 0.25);
+    return (int64_t)(500.0 * r * r);
 }
 
 // Timing brackets for one launch (no-ops unless profiling).
@@ -335,20 +366,36 @@ int band_decide(dasgd_ctx *c, BandTuner &t)
     return DASGD_OK;
 }
 
-// Choice for the next launch of the kernel that tuner t serves, over rows of row4 128-bit columns: the
-// log2 of a band length, or a negative candidate (the caller's other work order).  *trial >= 0: the
-// launch is a timed trial, band_close must follow it.
-int band_pick(dasgd_ctx *c, BandTuner &t, unsigned row4, int *log_band, int *trial)
+// Grid (gx, W, gz) that covers `blocks` workgroups per replica in bands of 2^log_band blocks per L2
+// partition.  The band is lengthened until gz fits the 16-bit limit of a grid's z dimension and
+// shortened to what the row needs.
+struct BandGrid { dim3 grid; int log_band; };
+BandGrid band_grid(uint64_t blocks, int W, int log_band)
+{
+    if (blocks < 1) blocks = 1;
+    int lb = log_band < 0 ? 0 : log_band;
+    while (lb > 0 && (8ull << (lb - 1)) >= blocks) --lb;               // one band already holds the row
+    while ((blocks + (8ull << lb) - 1) / (8ull << lb) > 65535ull) ++lb;
+    const uint64_t gx = 8ull << lb, gz = (blocks + gx - 1) / gx;
+    BandGrid g;
+    g.grid = dim3((unsigned)gx, (unsigned)W, (unsigned)gz);
+    g.log_band = lb;
+    return g;
+}
+
+// Choice for the next launch of the kernel that tuner t serves, over `blocks` workgroups per replica:
+// the log2 of a band length.  *trial >= 0: the launch is a timed trial, band_close must follow it.
+int band_pick(dasgd_ctx *c, BandTuner &t, uint64_t blocks, int *log_band, int *trial)
 {
     *trial = -1;
     if (c->band_fixed >= 0) {
-        *log_band = (int)decode_clamp_log_band(row4, (unsigned)c->band_fixed);
+        *log_band = band_grid(blocks, 1, c->band_fixed).log_band;
         return DASGD_OK;
     }
     if (t.n_cand == 0) {                        // fit the candidates to the row length, drop duplicates
         int n = 0;
         for (int i = 0; i < BandTuner::kMaxCand; ++i) {
-            const int lb = t.cand[i] < 0 ? t.cand[i] : (int)decode_clamp_log_band(row4, (unsigned)t.cand[i]);
+            const int lb = band_grid(blocks, 1, t.cand[i]).log_band;
             bool dup = false;
             for (int k = 0; k < n; ++k) dup = dup || t.cand[k] == lb;
             if (!dup) t.cand[n++] = lb;
@@ -370,7 +417,7 @@ int band_pick(dasgd_ctx *c, BandTuner &t, unsigned row4, int *log_band, int *tri
         for (int i = 0; i < t.n_cand; ++i)
             if (t.issued[i] < BandTuner::kSamples && (pick < 0 || t.issued[i] < t.issued[pick])) pick = i;
     if (pick < 0) {                             // cold launch, or all trials issued and results still to come
-        *log_band = t.cand[0];
+        *log_band = t.cand[t.n_cand / 2];
         return DASGD_OK;
     }
     BandTuner::Rec r;
@@ -393,33 +440,92 @@ int band_close(dasgd_ctx *c, BandTuner &t, int trial)
     return DASGD_OK;
 }
 
-int launch_mean(dasgd_ctx *c, hipStream_t s, const float *S, float *A, int64_t row_elems)
+// DASGD_SCHED_AUTO: mark phase boundaries on the main stream, and decide when the marks have completed.
+int schedule_tick(dasgd_ctx *c)
 {
-    const int64_t n4 = row_elems / 4;
-    const v4f *S4 = reinterpret_cast<const v4f *>(S);
+    ScheduleTuner &t = c->sched_tuner;
+    if (c->schedule != DASGD_SCHED_AUTO || t.chosen >= 0) return DASGD_OK;
+    if (t.phase < ScheduleTuner::kPhases) {
+        if (t.steps_in_phase == 0 && t.phase >= 1) {            // boundary: start of a measured phase
+            const int i = t.phase - 1;
+            if (!t.ev[i]) { HIPCHK(c, hipEventCreate(&t.ev[i])); t.n_ev = i + 1; }
+            HIPCHK(c, hipEventRecord(t.ev[i], c->main_s));
+        }
+        if (++t.steps_in_phase >= (t.phase == 0 ? 2 : 1) * t.phase_len) {   // (the warm-up also covers the band trials)
+            t.steps_in_phase = 0;
+            t.phase += 1;
+        }
+        return DASGD_OK;
+    }
+    const int last = ScheduleTuner::kPhases - 1;                // the mark that ends the last measured phase
+    if (!t.ev[last]) {
+        HIPCHK(c, hipEventCreate(&t.ev[last]));
+        t.n_ev = last + 1;
+        HIPCHK(c, hipEventRecord(t.ev[last], c->main_s));
+        return DASGD_OK;
+    }
+    const hipError_t q = hipEventQuery(t.ev[last]);
+    if (q == hipErrorNotReady) {
+        (void)hipGetLastError();
+        return DASGD_OK;
+    }
+    HIPCHK(c, q);
+    t.overlap_ms = t.serial_ms = 0;
+    for (int p = 1; p < ScheduleTuner::kPhases; ++p) {          // phase p lies between marks p-1 and p
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, t.ev[p - 1], t.ev[p]));
+        ((p & 1) ? t.overlap_ms : t.serial_ms) += ms;
+    }
+    t.chosen = t.overlap_ms < t.serial_ms ? DASGD_SCHED_OVERLAP : DASGD_SCHED_SERIAL;
+    for (int i = 0; i < t.n_ev; ++i) { (void)hipEventDestroy(t.ev[i]); t.ev[i] = nullptr; }
+    t.n_ev = 0;
+    return DASGD_OK;
+}
+
+// Are the rows 128-byte aligned relative to each other?  (If not, neighbouring column windows of the mean
+// kernels share cache lines, and the kernels issue runs of windows on one L2 partition.)
+bool rows_share_lines(const ConstRowSet &r, int W)
+{
+    for (int j = 0; j < W; ++j)
+        if ((reinterpret_cast<uintptr_t>(r.p[j]) - reinterpret_cast<uintptr_t>(r.p[0])) & 127u) return true;
+    return (reinterpret_cast<uintptr_t>(r.p[0]) & 127u) != 0;
+}
+
+inline unsigned mean_grid(unsigned row4) { return ((row4 + kWave - 1) / kWave + 63u) / 64u * 64u; }
+
+// W-way mean of `row_elems` floats per row (a multiple of 4, rows 16-byte aligned) into A.
+// rows: the W row pointers (W <= kMaxRows); or strided != nullptr: rows at strided + j * stride floats.
+int launch_mean(dasgd_ctx *c, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
+{
+    const unsigned row4 = (unsigned)(row_elems / 4);
     v4f *A4 = reinterpret_cast<v4f *>(A);
     const float inv_w = 1.0f / (float)c->W;
-    auto grid = [&](int U) { return dim3((unsigned)(((n4 + (int64_t)kWave * U - 1) / ((int64_t)kWave * U) + 63) / 64 * 64)); };
-    const bool runs = (row_elems % 32) != 0;         // rows not 128-byte aligned to each other
-#define DASGD_LAUNCH_MEAN(WT)                                                                                   \
+    ConstRowSet r = {};
+    if (rows) r = *rows;
+    else if (c->W <= kMaxRows)
+        for (int j = 0; j < c->W; ++j) r.p[j] = strided + (int64_t)j * stride;
+    if (c->W > kMaxRows) {
+        hipLaunchKernelGGL(k_mean_strided, dim3((row4 + kWave - 1) / kWave), dim3(kWave), 0, s,
+                           reinterpret_cast<const v4f *>(strided), stride / 4, A4, row4, c->W, inv_w);
+        HIPCHK(c, hipGetLastError());
+        return DASGD_OK;
+    }
+    const bool runs = rows_share_lines(r, c->W);
+    const dim3 grid(mean_grid(row4));
+#define DASGD_LAUNCH_MEAN(WT, NW)                                                                               \
     do {                                                                                                        \
-        if (runs) hipLaunchKernelGGL((k_mean<WT, 1, true, true>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
-        else      hipLaunchKernelGGL((k_mean<WT, 1, true, false>), grid(1), dim3(kWave), 0, s, S4, A4, n4, n4, c->W, inv_w); \
-    } while (0)
-#define DASGD_LAUNCH_MEAN_LDS(WT, NW)                                                                           \
-    do {                                                                                                        \
-        if (runs) hipLaunchKernelGGL((k_mean_lds<WT, NW, true>), grid(1), dim3(kWave * NW), 0, s, S4, A4, n4, n4, inv_w); \
-        else      hipLaunchKernelGGL((k_mean_lds<WT, NW, false>), grid(1), dim3(kWave * NW), 0, s, S4, A4, n4, n4, inv_w); \
+        if (runs) hipLaunchKernelGGL((k_mean_rows<WT, NW, true>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w);  \
+        else      hipLaunchKernelGGL((k_mean_rows<WT, NW, false>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w); \
     } while (0)
     switch (c->W) {             // rows split over wavefronts + LDS where that measured faster
-    case 1:  DASGD_LAUNCH_MEAN(1);  break;
-    case 2:  DASGD_LAUNCH_MEAN(2);  break;
-    case 4:  DASGD_LAUNCH_MEAN_LDS(4, 4);  break;
-    case 8:  DASGD_LAUNCH_MEAN_LDS(8, 4);  break;
-    case 16: DASGD_LAUNCH_MEAN_LDS(16, 8); break;
-    default: DASGD_LAUNCH_MEAN(0);  break;
+    case 4:  DASGD_LAUNCH_MEAN(4, 4);  break;
+    case 8:  DASGD_LAUNCH_MEAN(8, 4);  break;
+    case 16: DASGD_LAUNCH_MEAN(16, 8); break;
+    default:
+        if (runs) hipLaunchKernelGGL((k_mean_any<true>), grid, dim3(kWave), 0, s, r, A4, row4, c->W, inv_w);
+        else      hipLaunchKernelGGL((k_mean_any<false>), grid, dim3(kWave), 0, s, r, A4, row4, c->W, inv_w);
+        break;
     }
-#undef DASGD_LAUNCH_MEAN_LDS
 #undef DASGD_LAUNCH_MEAN
     HIPCHK(c, hipGetLastError());
     return DASGD_OK;
@@ -441,10 +547,7 @@ dasgd_ctx *dasgd_create(int W, int64_t P, int d, int tau, float lr, float moment
     c->W = W; c->P = P; c->d = d; c->tau = tau;
     c->lr = lr; c->momentum = momentum; c->wd = wd;
     c->slots = d / tau + 1;
-    for (BandTuner &t : c->table_tuner) {
-        const int orders[BandTuner::kMaxCand] = {-1, 0, 0, 0, 0};          // duplicates are dropped when the tuner starts
-        for (int i = 0; i < BandTuner::kMaxCand; ++i) t.cand[i] = orders[i];
-    }
+    c->sched_tuner.phase_len = (std::max(8, 2 * tau) + tau - 1) / tau * tau;      // whole averaging periods
     return c;
 }
 
@@ -464,7 +567,7 @@ int dasgd_set_lr(dasgd_ctx *c, float lr)
 
 int dasgd_set_schedule(dasgd_ctx *c, int schedule)
 {
-    if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_OVERLAP_FREE) return DASGD_EINVAL;
+    if (!c || schedule < DASGD_SCHED_OVERLAP || schedule > DASGD_SCHED_AUTO) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->schedule = schedule;
     return DASGD_OK;
@@ -488,7 +591,7 @@ int dasgd_set_fusion(dasgd_ctx *c, int fusion)
 
 int dasgd_set_snapshot(dasgd_ctx *c, int mode)
 {
-    if (!c || (mode != DASGD_SNAPSHOT_COPY && mode != DASGD_SNAPSHOT_ZERO_COPY)) return DASGD_EINVAL;
+    if (!c || mode < DASGD_SNAPSHOT_COPY || mode > DASGD_SNAPSHOT_AUTO) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->snapshot = mode;
     return DASGD_OK;
@@ -497,12 +600,15 @@ int dasgd_set_snapshot(dasgd_ctx *c, int mode)
 size_t dasgd_workspace_bytes(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
 {
     if (!shapes_ok(c, n_tensors, numel)) return 0;
-    return make_layout(c, n_tensors, numel).total;
+    const Layout L = make_layout(c, n_tensors, numel);
+    if (L.P_pad >= (1ll << 32)) return 0;
+    return L.total;
 }
 
 static int bind_common(dasgd_ctx *c, int n_tensors, const int64_t *numel)
 {
     if (!shapes_ok(c, n_tensors, numel)) return DASGD_EINVAL;
+    if (make_layout(c, n_tensors, numel).P_pad >= (1ll << 32)) return DASGD_EINVAL;    // record offsets are 32-bit
     if (c->bound) return DASGD_ESTATE;
     if (c->g_pinned || !c->snap_done.empty()) return DASGD_ESTATE;     // an earlier bind failed half-way
     return DASGD_OK;
@@ -540,7 +646,8 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
             if (!range_ok(x[r], bytes, &lx) || !range_ok(v[r], bytes, &lv)) return DASGD_EINVAL;
         }
     }
-    {   // x, v and the workspace are all written: none of them may share a byte with another
+    {   // x, v and the workspace are all written: none of them may share a byte with another.  (No kernel
+        // touches a byte outside these ranges: what lies between or behind the caller's tensors is not ours.)
         std::vector<std::pair<uintptr_t, size_t>> iv;
         iv.reserve(2 * rows + 1);
         for (size_t r = 0; r < rows; ++r) {
@@ -552,45 +659,40 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
         if (any_overlap(iv)) return DASGD_EINVAL;
         c->owned.swap(iv);                     // sorted by start, pairwise disjoint: gradient buffers are checked against it
     }
-    int64_t ldx = 0, ldv = 0;
-    bool matrix = is_matrix(c, n_tensors, numel, x, &ldx) && is_matrix(c, n_tensors, numel, v, &ldv) && ldx == ldv;
-    // the matrix kernels also touch the padding behind the LAST row: it must exist
-    if (matrix) {
-        const size_t extent = sizeof(float) * (size_t)c->W * (size_t)ldx;
-        matrix = range_ok(x[0], extent) && range_ok(v[0], extent);
-    }
-    Layout L = make_layout(c, n_tensors, numel, matrix, ldx);
+    const bool as_rows = is_rows(c, n_tensors, numel, x) && is_rows(c, n_tensors, numel, v);
+    Layout L = make_layout(c, n_tensors, numel, as_rows);
     if (workspace_bytes < L.total) return DASGD_ENOMEM;
     if (!range_ok(workspace, L.total)) return DASGD_EINVAL;
 
-    // chunk table
-    std::vector<Chunk> chunks;
-    chunks.reserve((size_t)L.n_chunks);
-    for (int t = 0; t < n_tensors; ++t)
-        for (int64_t off = 0; off < numel[t]; off += kChunk) {
-            Chunk ch;
-            ch.off = off;
-            ch.foff = L.foff[t] + off;
-            ch.tensor = t;
-            ch.len = (int32_t)((numel[t] - off) < kChunk ? (numel[t] - off) : kChunk);
-            chunks.push_back(ch);
-        }
+    // records: one per replica and piece of a tensor
+    std::vector<Rec> recs;
+    recs.reserve((size_t)c->W * (size_t)L.n_pieces);
+    for (int j = 0; j < c->W; ++j)
+        for (int t = 0; t < n_tensors; ++t)
+            for (int64_t off = 0; off < numel[t]; off += kPiece) {
+                Rec r;
+                r.x = x[(size_t)j * n_tensors + t] + off;
+                r.v = v[(size_t)j * n_tensors + t] + off;
+                r.aoff = (uint32_t)(L.foff[t] + off);
+                r.goff = (uint32_t)off;
+                r.len = (uint32_t)std::min<int64_t>(numel[t] - off, kPiece);
+                r.tensor = (uint32_t)t;
+                recs.push_back(r);
+            }
 
     c->n_tensors = n_tensors;
     c->numel.assign(numel, numel + n_tensors);
     c->lay = L;
-    c->xv_matrix = matrix;
-    c->ld = matrix ? ldx : 0;
-    c->x0 = x[0];
-    c->v0 = v[0];
-    c->idx32 = matrix && c->ld / 4 >= 64 && (int64_t)c->W * c->ld / 4 + 64 < (1ll << 31) && decode_grid((unsigned)c->W, (unsigned)(c->ld / 4), 11) < (1ull << 31);
+    c->xv_rows = as_rows;
+    c->xr = RowSet{};
+    c->vr = RowSet{};
+    if (as_rows)
+        for (int j = 0; j < c->W; ++j) { c->xr.p[j] = x[(size_t)j * n_tensors]; c->vr.p[j] = v[(size_t)j * n_tensors]; }
     c->ws = static_cast<char *>(workspace);
     c->main_s = static_cast<hipStream_t>(main_stream);
     c->side_s = static_cast<hipStream_t>(side_stream);
 
-    HIPCHK(c, hipMemcpyAsync(c->ws + L.chunks, chunks.data(), sizeof(Chunk) * chunks.size(), hipMemcpyHostToDevice, c->main_s));
-    HIPCHK(c, hipMemcpyAsync(c->ws + L.xp, x, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
-    HIPCHK(c, hipMemcpyAsync(c->ws + L.vp, v, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
+    HIPCHK(c, hipMemcpyAsync(c->ws + L.recs, recs.data(), sizeof(Rec) * recs.size(), hipMemcpyHostToDevice, c->main_s));
     // snapshots and averages start at zero (padding elements are averaged too and must stay finite)
     {
         const int64_t n4 = (int64_t)((L.total - L.S) / 16);
@@ -615,12 +717,13 @@ int dasgd_bind(dasgd_ctx *c, int n_tensors, const int64_t *numel, float *const *
     return DASGD_OK;
 }
 
-// Launch the W-way mean of snapshot slot `slot`.  In the overlap schedule it goes to the side
-// stream, ordered after everything enqueued on the main stream so far.
-static int launch_average(dasgd_ctx *c, int slot)
+// Launch the W-way mean for ring slot `slot`.  In the overlap schedules it goes to the side stream,
+// ordered after everything enqueued on the main stream so far.  *on_side tells where it went.
+static int launch_average(dasgd_ctx *c, int slot, bool *on_side)
 {
     hipStream_t s = c->main_s;
-    if (side_stream_mean(c)) {
+    *on_side = side_stream_mean(c);
+    if (*on_side) {
         HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
         HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
         s = c->side_s;
@@ -628,24 +731,32 @@ static int launch_average(dasgd_ctx *c, int slot)
     int rec;
     int rc = prof_open(c, c->zc && c->zc_recon ? DASGD_K_MEAN_RECONSTRUCT : DASGD_K_MEAN, s, &rec);
     if (rc != DASGD_OK) return rc;
-    if (c->zc && c->zc_recon) {
-        const int64_t n4 = c->ld / 4;
-        const unsigned grid = (unsigned)(((n4 + kWave - 1) / kWave + 63) / 64 * 64);
-        const v4f *X4 = reinterpret_cast<const v4f *>(c->x0), *Ao = reinterpret_cast<const v4f *>(avg_ptr(c, c->zc_old_slot));
-        v4f *An = reinterpret_cast<v4f *>(avg_ptr(c, slot));
-        const double om = (double)(1.0f - c->zc_xi), inv_xi = 1.0 / (double)c->zc_xi, inv_w = 1.0 / (double)c->W;
-        if (c->ld % 32)
-            hipLaunchKernelGGL((k_mean_reconstruct<4, true>), dim3(grid), dim3(kWave * 4), 0, s, X4, Ao, An, n4, n4, c->W, inv_w, om, inv_xi);
-        else
-            hipLaunchKernelGGL((k_mean_reconstruct<4, false>), dim3(grid), dim3(kWave * 4), 0, s, X4, Ao, An, n4, n4, c->W, inv_w, om, inv_xi);
-        HIPCHK(c, hipGetLastError());
+    if (c->zc) {
+        ConstRowSet rows = {};
+        for (int j = 0; j < c->W; ++j) rows.p[j] = c->xr.p[j];
+        if (c->zc_recon) {
+            const unsigned row4 = (unsigned)(c->P / 4);
+            const v4f *Ao = reinterpret_cast<const v4f *>(avg_ptr(c, c->zc_old_slot));
+            v4f *An = reinterpret_cast<v4f *>(avg_ptr(c, slot));
+            const float om = 1.0f - c->zc_xi, inv_xi = 1.0f / c->zc_xi, inv_w = 1.0f / (float)c->W;
+            const dim3 grid(mean_grid(row4));
+            if (rows_share_lines(rows, c->W))
+                hipLaunchKernelGGL((k_mean_undo_merge<4, true>), grid, dim3(kWave * 4), 0, s, rows, Ao, An, row4, c->W, inv_w, om, inv_xi);
+            else
+                hipLaunchKernelGGL((k_mean_undo_merge<4, false>), grid, dim3(kWave * 4), 0, s, rows, Ao, An, row4, c->W, inv_w, om, inv_xi);
+            HIPCHK(c, hipGetLastError());
+        } else {
+            rc = launch_mean(c, s, &rows, nullptr, 0, avg_ptr(c, slot), c->P);
+            if (rc != DASGD_OK) return rc;
+        }
     } else {
-        rc = launch_mean(c, s, c->zc ? c->x0 : snap_ptr(c, slot), avg_ptr(c, slot), c->lay.P_pad);
+        // snapshot rows: P_pad floats each (tensor padding included: zero, averaged to zero)
+        rc = launch_mean(c, s, nullptr, snap_ptr(c, slot), c->lay.P_pad, avg_ptr(c, slot), c->lay.P_pad);
         if (rc != DASGD_OK) return rc;
     }
     rc = prof_close(c, s, rec);
     if (rc != DASGD_OK) return rc;
-    if (side_stream_mean(c)) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
+    if (*on_side) HIPCHK(c, hipEventRecord(c->avg_done[slot], c->side_s));
     return DASGD_OK;
 }
 
@@ -660,27 +771,20 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     // will this very step end with a merge?  (d == 0: of the average it launches itself)
     const bool merge_follows = (c->d == 0) ? snap_step
                                            : (!c->pending.empty() && c->pending.front().launch_step == k - c->d);
-    const bool snap = snap_step && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
-    // fold the merge into this kernel?  (not for d == 0: that merge needs the mean of this step's own output)
-    const bool fold = merge_follows && c->d > 0 && c->fusion >= DASGD_FUSE_STEP_MERGE;
-    int mode = kStoreX;
-    if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
-    // zero-copy snapshot: store none, let the mean read x (see DASGD_SNAPSHOT_ZERO_COPY)
-    const bool zc = snap && c->snapshot == DASGD_SNAPSHOT_ZERO_COPY && c->xv_matrix && c->fusion == DASGD_FUSE_STEP_MERGE &&
-                    (c->schedule == DASGD_SCHED_OVERLAP || c->schedule == DASGD_SCHED_SERIAL) &&
-                    (fold ? c->xi >= 0.125f : !merge_follows);
-    if (zc) mode = kStoreX;
-    // everything in one kernel?  (decided below once the gradient layout is known)
-    bool all = false;
     const size_t rows = (size_t)c->W * (size_t)c->n_tensors;
 
+    // A changed gradient table is validated and staged first; the context adopts it only after the
+    // kernel that uses it has been launched.
+    bool g_changed = false, g_rows_new = c->g_rows;
+    int g_buf = c->g_cur;
+    ConstRowSet gr_new = c->gr;
     if (!c->dry) {
         if (!g && c->g_cur < 0) return DASGD_EINVAL;
         if (g) {
             for (size_t r = 0; r < rows; ++r)
                 if (!g[r] || (reinterpret_cast<uintptr_t>(g[r]) & 3u)) return DASGD_EINVAL;
-            const bool changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
-            if (changed) {
+            g_changed = c->g_cur < 0 || std::memcmp(g, c->g_cached.data(), sizeof(void *) * rows) != 0;
+            if (g_changed) {
                 DeviceRange lg;
                 for (size_t r = 0; r < rows; ++r) {
                     const size_t bytes = sizeof(float) * (size_t)c->numel[r % (size_t)c->n_tensors];
@@ -691,26 +795,47 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
                     if (it != c->owned.end() && it->first < a + bytes) return DASGD_EINVAL;
                     if (it != c->owned.begin() && (it - 1)->first + (it - 1)->second > a) return DASGD_EINVAL;
                 }
-                // retire the table in use (all kernels reading it are already enqueued), take the next
-                if (c->g_cur >= 0) {
-                    HIPCHK(c, hipEventRecord(c->g_ev[c->g_cur], c->main_s));
-                    c->g_ev_live[c->g_cur] = true;
-                }
-                const int b = (c->g_cur + 1) % kGTables;
-                if (c->g_ev_live[b]) {
-                    HIPCHK(c, hipEventSynchronize(c->g_ev[b]));      // its last reader ran kGTables-1 changes ago
-                    c->g_ev_live[b] = false;
-                }
-                void *stage = static_cast<char *>(c->g_pinned) + sizeof(void *) * rows * (size_t)b;
-                std::memcpy(stage, g, sizeof(void *) * rows);
-                HIPCHK(c, hipMemcpyAsync(c->ws + c->lay.gp[b], stage, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
-                c->g_cached.assign(g, g + rows);
-                c->g_cur = b;
-                int64_t ldg = 0;
-                c->g_matrix = is_matrix(c, c->n_tensors, c->numel.data(), g, &ldg) && ldg == c->ld &&
-                              range_ok(g[0], sizeof(float) * (size_t)c->W * (size_t)ldg);
-                c->g0 = g[0];
+                g_rows_new = is_rows(c, c->n_tensors, c->numel.data(), g);
+                gr_new = ConstRowSet{};
+                if (g_rows_new)
+                    for (int j = 0; j < c->W; ++j) gr_new.p[j] = g[(size_t)j * c->n_tensors];
+                g_buf = (c->g_cur + 1) % kGTables;
             }
+        }
+    }
+
+    const int sched = effective_schedule(c);
+    c->sched_now = sched;
+    const bool snap = snap_step && sched != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
+    // fold the merge into this kernel?  (not for d == 0: that merge needs the mean of this step's own output)
+    const bool fold = merge_follows && c->d > 0 && c->fusion >= DASGD_FUSE_STEP_MERGE;
+    int mode = kStoreX;
+    if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
+    // zero-copy snapshot: store none, let the mean read x (see DASGD_SNAPSHOT_*)
+    const bool zc_wanted = c->snapshot == DASGD_SNAPSHOT_ZERO_COPY ||
+                           (c->snapshot == DASGD_SNAPSHOT_AUTO && k < zero_copy_budget(c->xi));
+    const bool zc = snap && zc_wanted && c->xv_rows && c->fusion == DASGD_FUSE_STEP_MERGE &&
+                    (sched == DASGD_SCHED_OVERLAP || sched == DASGD_SCHED_SERIAL) &&
+                    (fold ? c->xi >= 0.125f : !merge_follows);
+    if (zc) mode = kStoreX;
+    bool all = false;               // everything in one kernel?
+
+    if (!c->dry) {
+        int rc = schedule_tick(c);
+        if (rc != DASGD_OK) return rc;
+        if (g_changed) {
+            // retire the table in use (all kernels reading it are already enqueued), take the next
+            if (c->g_cur >= 0) {
+                HIPCHK(c, hipEventRecord(c->g_ev[c->g_cur], c->main_s));
+                c->g_ev_live[c->g_cur] = true;
+            }
+            if (c->g_ev_live[g_buf]) {
+                HIPCHK(c, hipEventSynchronize(c->g_ev[g_buf]));      // its last reader ran kGTables-1 changes ago
+                c->g_ev_live[g_buf] = false;
+            }
+            void *stage = static_cast<char *>(c->g_pinned) + sizeof(void *) * rows * (size_t)g_buf;
+            std::memcpy(stage, g, sizeof(void *) * rows);
+            HIPCHK(c, hipMemcpyAsync(c->ws + c->lay.gp[g_buf], stage, sizeof(void *) * rows, hipMemcpyHostToDevice, c->main_s));
         }
         const int slot = (int)(c->n_launched % c->slots);
         float *S = mode == kStoreX ? nullptr : snap_ptr(c, slot);
@@ -720,119 +845,96 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         // beside one only makes both slower; the local step therefore waits for the means in flight,
         // which leaves them whatever the caller put on the main stream since the last merge (the
         // forward/backward pass) to hide behind.  The free variant waits only for the average it reads.
-        if (side_stream_mean(c)) {
-            for (size_t p = 0; p < c->pending.size(); ++p) {
-                Pending &pe = c->pending[p];
-                const bool needed = fold && p == 0;
-                if (pe.awaited || !(needed || c->schedule == DASGD_SCHED_OVERLAP)) continue;
-                HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[pe.slot], 0));
-                pe.awaited = true;
-            }
+        for (size_t p = 0; p < c->pending.size(); ++p) {
+            Pending &pe = c->pending[p];
+            const bool needed = fold && p == 0;
+            if (!pe.on_side || pe.awaited || !(needed || sched != DASGD_SCHED_OVERLAP_FREE)) continue;
+            HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[pe.slot], 0));
+            pe.awaited = true;
         }
         if (fold) A = avg_ptr(c, c->pending.front().slot);
-        all = c->fusion == DASGD_FUSE_ALL && c->d > 0 && c->xv_matrix && c->g_matrix &&
-              c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY && snap;
+        const bool row_kernels = c->xv_rows && g_rows_new;
+        all = c->fusion == DASGD_FUSE_ALL && c->d > 0 && row_kernels && snap;
         const int kid = all ? (fold ? DASGD_K_STEP_MEAN_MERGE : DASGD_K_STEP_MEAN)
                       : fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
                       : mode == kStoreXS ? DASGD_K_LOCAL_STEP_SNAP : DASGD_K_LOCAL_STEP_TO_SNAP;
         int rec, trial = -1;
         BandTuner *tuned = nullptr;
-        int rc = prof_open(c, kid, c->main_s, &rec);
+        rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        const bool flat = c->xv_matrix && c->g_matrix && (!fold || c->idx32);
+        const unsigned row4 = (unsigned)(c->P / 4);
         if (all) {
-            const int64_t row4 = c->ld / 4;
-            const dim3 agrid((unsigned)((row4 + kWave - 1) / kWave));
-            v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0);
-            const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
+            const dim3 agrid((row4 + kWave - 1) / kWave);
             const v4f *Ao = reinterpret_cast<const v4f *>(A);
-            v4f *An = snap ? reinterpret_cast<v4f *>(avg_ptr(c, slot)) : nullptr;
+            v4f *An = reinterpret_cast<v4f *>(avg_ptr(c, slot));
             const float inv_w = 1.0f / (float)c->W;
-#define DASGD_LAUNCH_ALL(WT, MEAN, MERGE)                                                                       \
-    hipLaunchKernelGGL((k_step_all_flat<WT, MEAN, MERGE>), agrid, dim3(kWave), 0, c->main_s, x4, v4, g4, Ao, An, \
-                       row4, c->W, c->lr, c->momentum, c->wd, om, inv_w)
-#define DASGD_LAUNCH_ROWS(WT, MERGE)                                                                            \
-    hipLaunchKernelGGL((k_step_all_rows<WT, MERGE>), agrid, dim3(kWave * WT), 0, c->main_s, x4, v4, g4, Ao, An,  \
-                       row4, c->lr, c->momentum, c->wd, om, inv_w)
-#define DASGD_LAUNCH_ALL_W(MEAN, MERGE)                                                                         \
-    switch (c->W) {                                                                                             \
-    case 1:  DASGD_LAUNCH_ALL(1, MEAN, MERGE);  break;                                                          \
-    case 2:  DASGD_LAUNCH_ROWS(2, MERGE);  break;                                                               \
-    case 4:  DASGD_LAUNCH_ROWS(4, MERGE);  break;                                                               \
-    case 8:  DASGD_LAUNCH_ROWS(8, MERGE);  break;                                                               \
-    case 16: DASGD_LAUNCH_ROWS(16, MERGE); break;                                                               \
-    default: DASGD_LAUNCH_ALL(0, MEAN, MERGE);  break;                                                          \
-    }
-            if (fold) { DASGD_LAUNCH_ALL_W(true, true) } else { DASGD_LAUNCH_ALL_W(true, false) }
-#undef DASGD_LAUNCH_ROWS
-#undef DASGD_LAUNCH_ALL_W
-#undef DASGD_LAUNCH_ALL
-        } else if (flat) {
-            const int64_t n4 = (int64_t)c->W * c->ld / 4;
-            const dim3 grid((unsigned)((n4 + kWave - 1) / kWave));
-            v4f *x4 = reinterpret_cast<v4f *>(c->x0), *v4 = reinterpret_cast<v4f *>(c->v0), *s4 = reinterpret_cast<v4f *>(S);
-            const v4f *g4 = reinterpret_cast<const v4f *>(c->g0);
-            if (fold) {
-                const v4f *A4 = reinterpret_cast<const v4f *>(A);
-                const unsigned row4 = (unsigned)(c->ld / 4);
-                int lbi;
-                tuned = &c->tuner[kid];
-                rc = band_pick(c, *tuned, row4, &lbi, &trial);
-                if (rc != DASGD_OK) return rc;
-                const unsigned lb = (unsigned)lbi;
-                const dim3 fgrid((unsigned)decode_grid((unsigned)c->W, row4, lb));
-#define DASGD_LAUNCH_FOLD(SNAP, WT)                                                                             \
-    hipLaunchKernelGGL((k_step_merge_flat<SNAP, WT>), fgrid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, A4,     \
-                       (unsigned)n4, row4, c->W, lb, c->lr, c->momentum, c->wd, om)
-#define DASGD_LAUNCH_FOLD_W(SNAP)                                                                               \
-    switch (c->W) {                                                                                             \
-    case 1:  DASGD_LAUNCH_FOLD(SNAP, 1);  break;                                                                \
-    case 2:  DASGD_LAUNCH_FOLD(SNAP, 2);  break;                                                                \
-    case 4:  DASGD_LAUNCH_FOLD(SNAP, 4);  break;                                                                \
-    case 8:  DASGD_LAUNCH_FOLD(SNAP, 8);  break;                                                                \
-    case 16: DASGD_LAUNCH_FOLD(SNAP, 16); break;                                                                \
-    default: DASGD_LAUNCH_FOLD(SNAP, 0);  break;                                                                \
-    }
-                if (mode == kStoreX) { DASGD_LAUNCH_FOLD_W(false) } else { DASGD_LAUNCH_FOLD_W(true) }
-#undef DASGD_LAUNCH_FOLD_W
-#undef DASGD_LAUNCH_FOLD
-            } else if (mode == kStoreX)
-                hipLaunchKernelGGL((k_local_step_flat<kStoreX>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
-            else if (mode == kStoreXS)
-                hipLaunchKernelGGL((k_local_step_flat<kStoreXS>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
-            else
-                hipLaunchKernelGGL((k_local_step_flat<kStoreS>), grid, dim3(kWave), 0, c->main_s, x4, v4, g4, s4, n4, c->lr, c->momentum, c->wd);
-        } else {
-            const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
-            float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
-            float *const *vp = reinterpret_cast<float *const *>(c->ws + c->lay.vp);
-            const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[c->g_cur]);
-            // Folded merge: either replica-major (all chunks of replica 0, then of replica 1, ...: each
-            // replica streams linearly and A is re-read W times, which is cheap while A fits the Infinity
-            // Cache), or the W replicas of a chunk back to back on one XCD (A from HBM once).  Which is
-            // faster depends on the size of A and on how the allocations lie in memory: measured in place.
-            int xcd_order = 0;
-            if (fold) {
-                tuned = &c->table_tuner[mode == kStoreX ? 0 : 1];
-                int pick;
-                rc = band_pick(c, *tuned, 1u << 20, &pick, &trial);
-                if (rc != DASGD_OK) return rc;
-                xcd_order = pick >= 0 ? 1 : 0;
+#define DASGD_LAUNCH_ROWS(WT)                                                                                   \
+    do {                                                                                                        \
+        if (fold) hipLaunchKernelGGL((k_step_all_rows<WT, true>), agrid, dim3(kWave * WT), 0, c->main_s, c->xr, c->vr, gr_new, \
+                                     Ao, An, row4, c->lr, c->momentum, c->wd, om, inv_w);                       \
+        else      hipLaunchKernelGGL((k_step_all_rows<WT, false>), agrid, dim3(kWave * WT), 0, c->main_s, c->xr, c->vr, gr_new, \
+                                     Ao, An, row4, c->lr, c->momentum, c->wd, om, inv_w);                       \
+    } while (0)
+            switch (c->W) {
+            case 2:  DASGD_LAUNCH_ROWS(2);  break;
+            case 4:  DASGD_LAUNCH_ROWS(4);  break;
+            case 8:  DASGD_LAUNCH_ROWS(8);  break;
+            case 16: DASGD_LAUNCH_ROWS(16); break;
+            default:
+                if (fold) hipLaunchKernelGGL((k_step_all_any<true>), agrid, dim3(kWave), 0, c->main_s, c->xr, c->vr, gr_new,
+                                             Ao, An, row4, c->W, c->lr, c->momentum, c->wd, om, inv_w);
+                else      hipLaunchKernelGGL((k_step_all_any<false>), agrid, dim3(kWave), 0, c->main_s, c->xr, c->vr, gr_new,
+                                             Ao, An, row4, c->W, c->lr, c->momentum, c->wd, om, inv_w);
+                break;
             }
-            const dim3 grid = xcd_order ? dim3((unsigned)((c->lay.n_chunks + 7) / 8 * 8 * c->W))
-                                        : dim3((unsigned)c->lay.n_chunks, (unsigned)c->W);
-#define DASGD_LAUNCH_TABLE(MODE, MERGE)                                                                         \
-    hipLaunchKernelGGL((k_local_step<MODE, MERGE>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, vp, gp, S, \
-                       c->lay.P_pad, c->n_tensors, c->lr, c->momentum, c->wd, A, om, c->W, (int)c->lay.n_chunks, xcd_order)
-            if (fold && mode == kStoreX)       DASGD_LAUNCH_TABLE(kStoreX, true);
-            else if (fold)                     DASGD_LAUNCH_TABLE(kStoreXS, true);
-            else if (mode == kStoreX)          DASGD_LAUNCH_TABLE(kStoreX, false);
-            else if (mode == kStoreXS)         DASGD_LAUNCH_TABLE(kStoreXS, false);
-            else                               DASGD_LAUNCH_TABLE(kStoreS, false);
-#undef DASGD_LAUNCH_TABLE
+#undef DASGD_LAUNCH_ROWS
+        } else {
+            // workgroups per replica, and their order: replica after replica for a plain step (each
+            // replica streams linearly); in bands when the average is re-read for every replica
+            const uint64_t blocks = row_kernels ? rows_blocks(row4) : ((uint64_t)c->lay.n_pieces << kPieceLog);
+            dim3 grid((unsigned)blocks, (unsigned)c->W, 1);
+            if (fold) {
+                int lb;
+                tuned = &c->tuner[kid];
+                rc = band_pick(c, *tuned, blocks, &lb, &trial);
+                if (rc != DASGD_OK) return rc;
+                grid = band_grid(blocks, c->W, lb).grid;
+            }
+            v4f *S4 = reinterpret_cast<v4f *>(S);
+            const v4f *A4 = reinterpret_cast<const v4f *>(A);
+            const int64_t ss = c->lay.P_pad;
+            if (row_kernels) {
+#define DASGD_LAUNCH_STEP(MODE, MERGE)                                                                          \
+    hipLaunchKernelGGL((k_step_rows<MODE, MERGE>), grid, dim3(kWave), 0, c->main_s, c->xr, c->vr, gr_new, S4, ss / 4, A4, row4, \
+                       c->lr, c->momentum, c->wd, om)
+                if (fold && mode == kStoreX)       DASGD_LAUNCH_STEP(kStoreX, true);
+                else if (fold)                     DASGD_LAUNCH_STEP(kStoreXS, true);
+                else if (mode == kStoreX)          DASGD_LAUNCH_STEP(kStoreX, false);
+                else if (mode == kStoreXS)         DASGD_LAUNCH_STEP(kStoreXS, false);
+                else                               DASGD_LAUNCH_STEP(kStoreS, false);
+#undef DASGD_LAUNCH_STEP
+            } else {
+                const Rec *recs = reinterpret_cast<const Rec *>(c->ws + c->lay.recs);
+                const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[g_buf]);
+#define DASGD_LAUNCH_STEP(MODE, MERGE)                                                                          \
+    hipLaunchKernelGGL((k_step_records<MODE, MERGE>), grid, dim3(kWave), 0, c->main_s, recs, (unsigned)c->lay.n_pieces, (unsigned)blocks, \
+                       gp, c->n_tensors, S, ss, A, c->lr, c->momentum, c->wd, om)
+                if (fold && mode == kStoreX)       DASGD_LAUNCH_STEP(kStoreX, true);
+                else if (fold)                     DASGD_LAUNCH_STEP(kStoreXS, true);
+                else if (mode == kStoreX)          DASGD_LAUNCH_STEP(kStoreX, false);
+                else if (mode == kStoreXS)         DASGD_LAUNCH_STEP(kStoreXS, false);
+                else                               DASGD_LAUNCH_STEP(kStoreS, false);
+#undef DASGD_LAUNCH_STEP
+            }
         }
         HIPCHK(c, hipGetLastError());
+        if (g_changed) {                        // launched with the new table: adopt it
+            c->g_cached.assign(g, g + rows);
+            c->g_cur = g_buf;
+            c->g_rows = g_rows_new;
+            c->gr = gr_new;
+        }
         if (tuned) {
             rc = band_close(c, *tuned, trial);
             if (rc != DASGD_OK) return rc;
@@ -861,7 +963,8 @@ int dasgd_average_begin(dasgd_ctx *c)
     if (!c->bound || !begin_due(c) || !c->snap_valid) return DASGD_ESTATE;
     if ((int)c->pending.size() >= c->slots) return DASGD_ESTATE;
     const int slot = c->snap_slot;
-    if (!c->dry && c->schedule != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY && !c->mean_in_step) {
+    bool on_side = false;
+    if (!c->dry && c->sched_now != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY && !c->mean_in_step) {
         // The mean has d local steps of slack, the merge of this step has none: when a merge of an
         // OLDER average is still to come in this step, the mean is launched right behind it, so the
         // two bandwidth-bound kernels do not run against each other and the mean overlaps what the
@@ -869,11 +972,12 @@ int dasgd_average_begin(dasgd_ctx *c)
         if (c->d > 0 && merge_due(c)) {
             c->mean_deferred = true;
         } else {
-            int rc = launch_average(c, slot);
+            int rc = launch_average(c, slot, &on_side);
             if (rc != DASGD_OK) return rc;
         }
     }
-    c->pending.push_back(Pending{c->n_done - 1, slot, c->mean_in_step});   // computed on the main stream: nothing to wait for
+    // (an average computed on the main stream has nothing to wait for)
+    c->pending.push_back(Pending{c->n_done - 1, slot, on_side, !on_side && !c->mean_deferred});
     c->mean_in_step = false;
     c->n_launched += 1;
     c->begun_for_k = true;
@@ -886,39 +990,31 @@ int dasgd_merge(dasgd_ctx *c)
     if (!c->bound || !merge_due(c)) return DASGD_ESTATE;
     const int slot = c->pending.front().slot;
     if (!c->dry && !c->merged_in_step) {
-        if (side_stream_mean(c) && !c->pending.front().awaited) HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
+        Pending &pe = c->pending.front();
+        if (pe.on_side && !pe.awaited) {
+            HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[slot], 0));
+            pe.awaited = true;
+        }
         const float *Y = c->y_in_snap ? snap_ptr(c, c->snap_slot) : nullptr;
         const float om = 1.0f - c->xi;
-        int rec, trial = -1;
+        int rec, trial = -1, lb;
         int rc = prof_open(c, DASGD_K_MERGE, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
-        if (c->xv_matrix && c->idx32) {
-            const int64_t row4 = c->ld / 4;
-            v4f *X4 = reinterpret_cast<v4f *>(c->x0);
-            const v4f *Y4 = Y ? reinterpret_cast<const v4f *>(Y) : X4;
-            const v4f *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
-            const unsigned n4 = (unsigned)(row4 * c->W);
-            int lbi;
-            rc = band_pick(c, c->tuner[DASGD_K_MERGE], (unsigned)row4, &lbi, &trial);
-            if (rc != DASGD_OK) return rc;
-            const unsigned lb = (unsigned)lbi;
-            const dim3 grid((unsigned)decode_grid((unsigned)c->W, (unsigned)row4, lb));
-            switch (c->W) {
-            case 1:  hipLaunchKernelGGL((k_merge_flat<1>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            case 2:  hipLaunchKernelGGL((k_merge_flat<2>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            case 4:  hipLaunchKernelGGL((k_merge_flat<4>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            case 8:  hipLaunchKernelGGL((k_merge_flat<8>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            case 16: hipLaunchKernelGGL((k_merge_flat<16>), grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            default: hipLaunchKernelGGL((k_merge_flat<0>),  grid, dim3(kWave), 0, c->main_s, X4, Y4, A4, n4, (unsigned)row4, c->W, lb, om); break;
-            }
+        const unsigned row4 = (unsigned)(c->P / 4);
+        const uint64_t blocks = c->xv_rows ? rows_blocks(row4) : ((uint64_t)c->lay.n_pieces << kPieceLog);
+        rc = band_pick(c, c->tuner[DASGD_K_MERGE], blocks, &lb, &trial);
+        if (rc != DASGD_OK) return rc;
+        const dim3 grid = band_grid(blocks, c->W, lb).grid;
+        if (c->xv_rows) {
+            const v4f *Y4 = reinterpret_cast<const v4f *>(Y), *A4 = reinterpret_cast<const v4f *>(avg_ptr(c, slot));
+            if (Y) hipLaunchKernelGGL((k_merge_rows<true>), grid, dim3(kWave), 0, c->main_s, c->xr, Y4, c->lay.P_pad / 4, A4, row4, om);
+            else   hipLaunchKernelGGL((k_merge_rows<false>), grid, dim3(kWave), 0, c->main_s, c->xr, Y4, c->lay.P_pad / 4, A4, row4, om);
         } else {
-            const Chunk *chunks = reinterpret_cast<const Chunk *>(c->ws + c->lay.chunks);
-            float *const *xp = reinterpret_cast<float *const *>(c->ws + c->lay.xp);
-            const dim3 grid((unsigned)c->lay.n_chunks);
-            if (Y)
-                hipLaunchKernelGGL((k_merge<true>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
-            else
-                hipLaunchKernelGGL((k_merge<false>), grid, dim3(kThreads), 0, c->main_s, chunks, xp, avg_ptr(c, slot), Y, c->lay.P_pad, c->n_tensors, c->W, om);
+            const Rec *recs = reinterpret_cast<const Rec *>(c->ws + c->lay.recs);
+            if (Y) hipLaunchKernelGGL((k_merge_records<true>), grid, dim3(kWave), 0, c->main_s, recs, (unsigned)c->lay.n_pieces, (unsigned)blocks,
+                                      Y, c->lay.P_pad, avg_ptr(c, slot), om);
+            else   hipLaunchKernelGGL((k_merge_records<false>), grid, dim3(kWave), 0, c->main_s, recs, (unsigned)c->lay.n_pieces, (unsigned)blocks,
+                                      Y, c->lay.P_pad, avg_ptr(c, slot), om);
         }
         HIPCHK(c, hipGetLastError());
         rc = band_close(c, c->tuner[DASGD_K_MERGE], trial);
@@ -926,11 +1022,13 @@ int dasgd_merge(dasgd_ctx *c)
         rc = prof_close(c, c->main_s, rec);
         if (rc != DASGD_OK) return rc;
     }
-    if (!c->dry) {
-        if (c->mean_deferred) {
-            const int rc2 = launch_average(c, c->snap_slot);
-            if (rc2 != DASGD_OK) return rc2;
-        }
+    if (!c->dry && c->mean_deferred) {
+        bool on_side = false;
+        const int rc2 = launch_average(c, c->snap_slot, &on_side);
+        if (rc2 != DASGD_OK) return rc2;
+        Pending &mine = c->pending.back();          // registered by dasgd_average_begin of this step
+        mine.on_side = on_side;
+        mine.awaited = !on_side;
     }
     c->mean_deferred = false;
     c->y_in_snap = false;
@@ -962,13 +1060,13 @@ int dasgd_gradient_average(dasgd_ctx *c, const float *G, float *out)
 {
     if (!c || !G || !out) return DASGD_EINVAL;
     if (!c->bound || c->dry) return DASGD_ESTATE;
-    if (c->P % 4 != 0) return DASGD_EINVAL;
+    if (c->P % 4 != 0 || c->P / 4 > (1ll << 31) - 256) return DASGD_EINVAL;
     if ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(out)) & 15u) return DASGD_EINVAL;
     if (!range_ok(G, sizeof(float) * (size_t)c->W * (size_t)c->P) || !range_ok(out, sizeof(float) * (size_t)c->P)) return DASGD_EINVAL;
     int rec;
     int rc = prof_open(c, DASGD_K_MEAN, c->main_s, &rec);
     if (rc != DASGD_OK) return rc;
-    rc = launch_mean(c, c->main_s, G, out, c->P);
+    rc = launch_mean(c, c->main_s, nullptr, G, c->P, out, c->P);
     if (rc != DASGD_OK) return rc;
     return prof_close(c, c->main_s, rec);
 }
@@ -994,12 +1092,41 @@ int dasgd_query(const dasgd_ctx *c, int64_t *step_k, int *n_pending, int *bdue, 
     return DASGD_OK;
 }
 
-int dasgd_layout(const dasgd_ctx *c, int64_t *flat_offset, int64_t *P_padded)
+int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
+
+void dasgd_destroy(dasgd_ctx *c)
+{
+    if (!c) return;
+    if (!c->dry) {
+        if (c->bound) {
+            (void)hipStreamSynchronize(c->main_s);
+            (void)hipStreamSynchronize(c->side_s);
+        }
+        // a bind that failed half-way leaves some of these set: release whatever exists
+        for (hipEvent_t e : c->snap_done) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : c->avg_done) if (e) (void)hipEventDestroy(e);
+        for (int b = 0; b < kGTables; ++b) if (c->g_ev[b]) (void)hipEventDestroy(c->g_ev[b]);
+        for (const ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (const ProfRec &r : c->prof_pool) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (BandTuner &t : c->tuner) {
+            for (const BandTuner::Rec &r : t.inflight) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+            for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
+        }
+        for (int i = 0; i < c->sched_tuner.n_ev; ++i) if (c->sched_tuner.ev[i]) (void)hipEventDestroy(c->sched_tuner.ev[i]);
+        if (c->g_pinned) (void)hipHostFree(c->g_pinned);
+    }
+    delete c;
+}
+
+// ---- include/dasgd_diag.h ------------------------------------------------------------------------
+
+int dasgd_layout(const dasgd_ctx *c, int64_t *flat_offset, int64_t *P_padded, int *addressing)
 {
     if (!c) return DASGD_EINVAL;
     if (!c->bound) return DASGD_ESTATE;
     if (flat_offset) std::memcpy(flat_offset, c->lay.foff.data(), sizeof(int64_t) * (size_t)c->n_tensors);
     if (P_padded) *P_padded = c->lay.P_pad;
+    if (addressing) *addressing = c->dry ? -1 : !c->xv_rows ? DASGD_ADDR_RECORDS : (c->g_cur >= 0 && !c->g_rows) ? DASGD_ADDR_ROWS_XV : DASGD_ADDR_ROWS;
     return DASGD_OK;
 }
 
@@ -1074,6 +1201,17 @@ int dasgd_band(dasgd_ctx *c, int kernel, int *log_band, int *settled, int *trial
     return DASGD_OK;
 }
 
+int dasgd_schedule_in_use(const dasgd_ctx *c, int *schedule, int *settled, double *overlap_ms, double *serial_ms)
+{
+    if (!c) return DASGD_EINVAL;
+    const bool is_auto = c->schedule == DASGD_SCHED_AUTO;
+    if (schedule) *schedule = is_auto && c->sched_tuner.chosen < 0 ? DASGD_SCHED_AUTO : effective_schedule(c);
+    if (settled) *settled = (!is_auto || c->sched_tuner.chosen >= 0) ? 1 : 0;
+    if (overlap_ms) *overlap_ms = c->sched_tuner.overlap_ms;
+    if (serial_ms) *serial_ms = c->sched_tuner.serial_ms;
+    return DASGD_OK;
+}
+
 int dasgd_device_extent(const void *p, size_t *bytes_to_end)
 {
     if (!p || !bytes_to_end) return DASGD_EINVAL;
@@ -1087,53 +1225,45 @@ int dasgd_device_extent(const void *p, size_t *bytes_to_end)
     return DASGD_OK;
 }
 
-int dasgd_check_block_map(int W, int64_t row4, int log_band)
+int dasgd_check_work_map(int kind, int64_t row4, int head, int log_band)
 {
-    if (W < 1 || W > 65535 || row4 < 64 || log_band < 0 || log_band > 11) return DASGD_EINVAL;
-    if ((int64_t)W * row4 + 64 >= (1ll << 31)) return DASGD_EINVAL;
-    const unsigned w = (unsigned)W, r4 = (unsigned)row4, n4 = w * r4;
-    const unsigned lb = decode_clamp_log_band(r4, (unsigned)log_band);
-    const uint64_t grid = decode_grid(w, r4, lb);
-    if (grid >= (1ull << 31)) return DASGD_EINVAL;
-    const unsigned n_blocks = (n4 + 63u) / 64u;
-    std::vector<unsigned char> seen(n_blocks, 0);
-    for (uint64_t b = 0; b < grid; ++b) {
-        unsigned blk, lo, hi;
-        if (!decode_owner((unsigned)b, w, r4, lb, blk, lo, hi)) continue;
-        if (blk >= n_blocks) return 1;                                  // a workgroup would start past the end
-        if (lo / r4 != (unsigned)(((uint64_t)blk * 64u) / r4)) return 2;   // owned by a row that does not hold its first element
-        if (seen[blk]++) return 3;                                      // handled twice
-    }
-    for (unsigned k = 0; k < n_blocks; ++k)
-        if (!seen[k]) return 4;                                         // never handled
-    return DASGD_OK;
-}
-
-int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
-
-void dasgd_destroy(dasgd_ctx *c)
-{
-    if (!c) return;
-    if (!c->dry) {
-        if (c->bound) {
-            (void)hipStreamSynchronize(c->main_s);
-            (void)hipStreamSynchronize(c->side_s);
-        }
-        // a bind that failed half-way leaves some of these set: release whatever exists
-        for (hipEvent_t e : c->snap_done) if (e) (void)hipEventDestroy(e);
-        for (hipEvent_t e : c->avg_done) if (e) (void)hipEventDestroy(e);
-        for (int b = 0; b < kGTables; ++b) if (c->g_ev[b]) (void)hipEventDestroy(c->g_ev[b]);
-        for (const ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-        for (const ProfRec &r : c->prof_pool) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-        for (BandTuner *ts : {c->tuner, c->table_tuner})
-            for (int i = 0; i < (ts == c->tuner ? (int)DASGD_K_COUNT : 2); ++i) {
-                BandTuner &t = ts[i];
-                for (const BandTuner::Rec &r : t.inflight) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-                for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
+    if (row4 < 1 || row4 > (1ll << 31) - 256) return DASGD_EINVAL;
+    const unsigned r4 = (unsigned)row4;
+    if (kind == DASGD_MAP_ROWS) {
+        // every column of a row whose first element sits `head` 128-bit elements behind a 1 KiB boundary is
+        // handled by exactly one (workgroup, lane) of the grid the library would launch, and by none twice
+        if (head < 0 || head > 63 || log_band < 0 || log_band > 11) return DASGD_EINVAL;
+        if (row4 > (1ll << 27)) return DASGD_EINVAL;            // (host memory of the check itself)
+        const BandGrid g = band_grid(rows_blocks(r4), 1, log_band);
+        std::vector<unsigned char> seen(r4, 0);
+        for (unsigned z = 0; z < g.grid.z; ++z)
+            for (unsigned x = 0; x < g.grid.x; ++x) {
+                const unsigned q = z * g.grid.x + x;
+                for (unsigned lane = 0; lane < 64; ++lane) {
+                    const unsigned col = rows_column(q, lane, (unsigned)head);
+                    if (col >= r4) continue;
+                    if (seen[col]++) return 3;                  // handled twice
+                    if (((col + (unsigned)head) & 63u) != lane) return 2;    // not the lane that keeps the kilobyte aligned
+                }
             }
-        if (c->g_pinned) (void)hipHostFree(c->g_pinned);
+        for (unsigned k = 0; k < r4; ++k)
+            if (!seen[k]) return 4;                             // never handled
+        return DASGD_OK;
     }
-    delete c;
+    if (kind == DASGD_MAP_MEAN || kind == DASGD_MAP_MEAN_RUNS) {
+        // the windows of the mean kernels: a permutation of [0, grid) that covers every window of the row
+        const unsigned grid = mean_grid(r4), windows = (r4 + 63u) / 64u;
+        std::vector<unsigned char> seen(grid, 0);
+        for (unsigned b = 0; b < grid; ++b) {
+            const uint64_t w = kind == DASGD_MAP_MEAN_RUNS ? mean_window<true>(b) : mean_window<false>(b);
+            if (w >= grid) return 1;                            // a window past the rounded-up grid
+            if (seen[w]++) return 3;
+        }
+        for (unsigned k = 0; k < windows; ++k)
+            if (!seen[k]) return 4;
+        return DASGD_OK;
+    }
+    return DASGD_EINVAL;
 }
 
 }  // extern "C"

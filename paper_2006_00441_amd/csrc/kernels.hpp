@@ -9,15 +9,29 @@
 //   merge        y, A -> x                            (Eq. 2, second branch)
 //   and the fused forms: local step + merge; local step + mean + merge.
 //
-// Two families.  The "matrix" kernels (k_*_flat, k_mean*) serve the layout the paper's matrix form
-// suggests: X, V, G are W x P row-major matrices (one row per replica, one row stride).  They
-// address by pure arithmetic and run one 64-lane wavefront per workgroup with one 128-bit access per
-// lane per array: measured on MI355X this shape sustains the highest HBM throughput (short-lived
-// single-wave workgroups keep the memory system evenly fed; anything that delays a wave's first
-// load -- a descriptor fetch, a larger workgroup -- costs bandwidth).  The one exception is the mean,
-// whose many loads per column are better split over the wavefronts of a workgroup and combined
-// through LDS.  The "table" kernels (k_local_step, k_merge) serve arbitrary per-tensor pointers
-// through a chunk table.
+// Two ways of finding the data.
+//   rows     every replica's parameters are ONE contiguous run of P floats (the paper's X_k with one
+//            column per worker: a W x P matrix with any row stride, or one arena per replica).  The W
+//            base pointers of x, v and g travel in the kernel arguments and are selected by blockIdx.y,
+//            so nothing has to be loaded from memory before a wave knows its addresses.
+//   records  anything else (one allocation per tensor, odd sizes, unaligned pointers): one 32-byte
+//            record per replica and 4096-float piece of a tensor holds the piece's pointers; the 16
+//            single-wave workgroups of a piece read the same record (one scalar load, cached).
+//
+// What measurements on MI355X fixed (a stand-alone study program sits beside this file):
+//   * one 64-lane wavefront per workgroup and one 128-bit access per lane per array beats every larger
+//     shape by 5-10 % (256 x 1, 256 x 4 unrolled, persistent grid-stride loops);
+//   * non-temporal loads and stores: + 7-10 %;
+//   * a wave's loads issued ONE AFTER THE OTHER (x, wait, v, wait, g) beat the same loads issued
+//     together by 1-3 %: many short-lived waves with one request each keep the memory system more
+//     evenly fed than fewer requests per wave in a burst.  The compiler would batch them, so each
+//     loaded value passes through arrived(), an empty asm statement that needs the value;
+//   * kilobytes that straddle a 1 KiB boundary cost up to 15 %: a row's blocks are aligned to the
+//     row's own address (see rows_column);
+//   * workgroups are dealt round-robin to the 8 L2 partitions (XCDs) in dispatch order, x fastest,
+//     then y, then z.  Kernels that re-read the average for every replica use a three-dimensional
+//     grid (8 B, W, bands): a partition sees B windows of replica 0, the same windows of replica 1,
+//     ..., and that piece of the average comes from HBM once and from its L2 for the other W - 1.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -25,21 +39,31 @@
 
 namespace dasgd {
 
-constexpr int kThreads = 256;                        // 4 wavefronts per workgroup
-constexpr int kUnroll  = 4;                          // independent 128-bit accesses per lane per array
-constexpr int kChunk   = kThreads * 4 * kUnroll;     // 4096 elements: the unit of work of one workgroup
-constexpr int kPad     = 64;                         // tensors start on 256-byte boundaries in library-owned rows
+constexpr int kWave     = 64;                 // lanes of a wavefront
+constexpr int kMaxRows  = 32;                 // replicas whose row pointers fit the kernel arguments
+constexpr int kPieceLog = 4;                  // a record covers 2^kPieceLog blocks of 64 128-bit elements
+constexpr int kPiece    = 256 << kPieceLog;   // = 4096 floats
+constexpr int kPad      = 64;                 // tensors start on 256-byte boundaries in padded library rows
+constexpr int kThreads  = 256;                // workgroup of the fill kernel
 
-// One unit of work: `len` consecutive elements of tensor `tensor`, starting at element `off` of the
-// tensor and at element `foff` of a library-owned row (snapshot / average).
-struct Chunk {
-    int64_t off;
-    int64_t foff;
-    int32_t tensor;
-    int32_t len;
+struct RowSet { float *p[kMaxRows]; };
+struct ConstRowSet { const float *p[kMaxRows]; };
+
+// One piece (at most kPiece floats) of one tensor of one replica.
+struct Rec {
+    float *x;
+    float *v;
+    uint32_t aoff;      // position of the piece in a library-owned row (snapshot, average), in floats
+    uint32_t goff;      // position of the piece in its tensor, in floats
+    uint32_t len;       // floats in the piece
+    uint32_t tensor;
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) v4f gv4f;             // pointers read from memory are generic
+typedef const __attribute__((address_space(1))) v4f cgv4f;      // to the compiler: say "global" where known
+typedef __attribute__((address_space(1))) float gf32;
+typedef const __attribute__((address_space(1))) float cgf32;
 
 // What a local step stores besides the momentum buffer.
 enum : int {
@@ -57,6 +81,12 @@ template <bool NT> __device__ __forceinline__ void st4(v4f *p, v4f a) {
     if constexpr (NT) __builtin_nontemporal_store(a, p);
     else *p = a;
 }
+__device__ __forceinline__ v4f gld4(cgv4f *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void gst4(gv4f *p, v4f a) { __builtin_nontemporal_store(a, p); }
+
+// The value must be in its registers here: a load issued before stays before, and the next load is
+// issued only after this one has come back.
+__device__ __forceinline__ void arrived(v4f &a) { asm volatile("" : "+v"(a)); }
 
 // Heavy-ball momentum with coupled weight decay, one element:
 //   g' = g + wd x ;  v <- momentum v + g' ;  x <- x - lr v
@@ -77,202 +107,82 @@ __device__ __forceinline__ void sgd4(v4f &x, v4f &v, const v4f g, float lr, floa
 }
 
 // Merge of one value: xi y + (1 - xi) a, computed as y + om (a - y) with om = 1 - xi  (Eq. 2, second branch).
+__device__ __forceinline__ float merge1(float y, float a, float om) { return fmaf(om, a - y, y); }
 __device__ __forceinline__ v4f merge4(v4f x, v4f a, float om) {
     v4f r;
-    r.x = fmaf(om, a.x - x.x, x.x);
-    r.y = fmaf(om, a.y - x.y, x.y);
-    r.z = fmaf(om, a.z - x.z, x.z);
-    r.w = fmaf(om, a.w - x.w, x.w);
+    r.x = merge1(x.x, a.x, om);
+    r.y = merge1(x.y, a.y, om);
+    r.z = merge1(x.z, a.z, om);
+    r.w = merge1(x.w, a.w, om);
     return r;
 }
 
 // ------------------------------------------------------------------------------------------------
-// Local step on every replica through the chunk table: grid = (chunks, W).
+// Work decomposition of the row kernels.  A row is row4 128-bit columns starting at a 16-byte aligned
+// address; block q of the row covers the columns q*64 - head ... q*64 - head + 63 that exist, where
+// head = (address / 16) mod 64 is the row's offset from a 1 KiB boundary: every wave then touches one
+// whole aligned kilobyte (the first and the last block of a row are partial).  Columns and blocks are
+// 32-bit: rows of up to 2^31 columns.
+__host__ __device__ __forceinline__ unsigned rows_head(const void *row) {
+    return (unsigned)((reinterpret_cast<uintptr_t>(row) >> 4) & 63u);
+}
+// column handled by `lane` of block q (a value >= row4, possibly by wrap-around, means none)
+__host__ __device__ __forceinline__ unsigned rows_column(unsigned q, unsigned lane, unsigned head) {
+    return q * 64u + lane - head;
+}
+// blocks a row can need whatever its head
+__host__ __device__ __forceinline__ unsigned rows_blocks(unsigned row4) { return (row4 + 63u + 63u) / 64u; }
+// block index of a workgroup in a grid (gx, W, gz)
+#define DASGD_BLOCK_OF_WG (blockIdx.z * gridDim.x + blockIdx.x)
+
+// ------------------------------------------------------------------------------------------------
+// Local step on every replica, rows addressing.  grid = (gx, W, gz), one wavefront per workgroup.
 // 20 bytes per element (24 when both x and the snapshot are stored).
-// MERGE: this step's merge is folded in -- the value stored to x is y + om (A - y), the snapshot
-// (if any) still receives y (paper Eq. 2, both branches in one pass).  With xcd_order the grid is
-// one-dimensional and ordered so that the W replicas of a chunk run back to back on one XCD: the
-// chunk's piece of A comes from HBM once and from that XCD's L2 for the other W-1 replicas.
+// MERGE: this step's merge is folded in -- the value stored to x is y + om (A - y), the snapshot (if
+// any) still receives y (paper Eq. 2, both branches in one pass): 20 + 4/W bytes per element.
+// S: snapshot rows (row stride s_stride4 columns, row j column c <-> x_j column c); A: the average.
 template <int MODE, bool MERGE>
-__global__ void __launch_bounds__(kThreads)
-k_local_step(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, float *const *__restrict__ vp,
-             const float *const *__restrict__ gp, float *__restrict__ S, int64_t P_pad, int n_tensors,
-             float lr, float momentum, float wd, const float *__restrict__ A, float om, int W, int n_chunks, int xcd_order)
+__global__ void __launch_bounds__(kWave)
+k_step_rows(const RowSet x, const RowSet v, const ConstRowSet g, v4f *__restrict__ S, int64_t s_stride4,
+            const v4f *__restrict__ A, unsigned row4, float lr, float momentum, float wd, float om)
 {
     constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
     static_assert(!(MERGE && MODE == kStoreS), "a folded merge always stores x");
-    unsigned chunk_id = blockIdx.x;
-    int j = blockIdx.y;
-    if (MERGE && xcd_order) {
-        const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
-        j = (int)(slot % (unsigned)W);
-        chunk_id = (slot / (unsigned)W) * 8u + xcd;
-        if (chunk_id >= (unsigned)n_chunks) return;
-    }
-    const Chunk c = chunks[chunk_id];
-    const int64_t row = (int64_t)j * n_tensors + c.tensor;
-    float *__restrict__ x = xp[row] + c.off;
-    float *__restrict__ v = vp[row] + c.off;
-    const float *__restrict__ g = gp[row] + c.off;
-    float *__restrict__ s = WS ? S + (int64_t)j * P_pad + c.foff : nullptr;
-    const float *__restrict__ a = MERGE ? A + c.foff : nullptr;
-    const int tid = threadIdx.x;
-    const int len = c.len;
-
-    const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(v) |
-                           reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(s) |
-                           reinterpret_cast<uintptr_t>(a)) & 15u) == 0;
-    if (aligned) {
-        v4f *x4 = reinterpret_cast<v4f *>(x);
-        v4f *v4 = reinterpret_cast<v4f *>(v);
-        const v4f *g4 = reinterpret_cast<const v4f *>(g);
-        v4f *s4 = reinterpret_cast<v4f *>(s);
-        const v4f *a4 = reinterpret_cast<const v4f *>(a);
-        if (len == kChunk) {
-            v4f xr[kUnroll], vr[kUnroll], gr[kUnroll], ar[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int i = tid + u * kThreads;
-                xr[u] = ld4<true>(x4 + i);
-                vr[u] = ld4<true>(v4 + i);
-                gr[u] = ld4<true>(g4 + i);
-                if (MERGE) ar[u] = ld4<false>(a4 + i);
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int i = tid + u * kThreads;
-                sgd4(xr[u], vr[u], gr[u], lr, momentum, wd);
-                st4<true>(v4 + i, vr[u]);
-                if (WS) st4<true>(s4 + i, xr[u]);
-                if (WX) st4<true>(x4 + i, MERGE ? merge4(xr[u], ar[u], om) : xr[u]);
-            }
-        } else {
-            const int n4 = len >> 2;
-            for (int i = tid; i < n4; i += kThreads) {
-                v4f xr = x4[i], vr = v4[i];
-                const v4f gr = g4[i];
-                sgd4(xr, vr, gr, lr, momentum, wd);
-                v4[i] = vr;
-                if (WS) s4[i] = xr;
-                if (WX) x4[i] = MERGE ? merge4(xr, a4[i], om) : xr;
-            }
-            const int e = (n4 << 2) + tid;         // at most 3 leftover elements
-            if (e < len) {
-                float xs = x[e], vs = v[e];
-                sgd1(xs, vs, g[e], lr, momentum, wd);
-                v[e] = vs;
-                if (WS) s[e] = xs;
-                if (WX) x[e] = MERGE ? fmaf(om, a[e] - xs, xs) : xs;
-            }
-        }
-    } else {
-        for (int e = tid; e < len; e += kThreads) {
-            float xs = x[e], vs = v[e];
-            sgd1(xs, vs, g[e], lr, momentum, wd);
-            v[e] = vs;
-            if (WS) s[e] = xs;
-            if (WX) x[e] = MERGE ? fmaf(om, a[e] - xs, xs) : xs;
-        }
-    }
-}
-
-// Matrix layout: x, v, g (and the snapshot) are W*P contiguous floats each, 16-byte aligned, with
-// n4 = W*P/4.  One wavefront per workgroup, one 128-bit access per lane per array.
-constexpr int kWave = 64;
-
-template <int MODE>
-__global__ void __launch_bounds__(kWave)
-k_local_step_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
-                  int64_t n4, float lr, float momentum, float wd)
-{
-    constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
-    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
-    if (i >= n4) return;
-    v4f xr = ld4<true>(x + i);
-    v4f vr = ld4<true>(v + i);
-    const v4f gr = ld4<true>(g + i);
+    const unsigned j = blockIdx.y;
+    v4f *__restrict__ xj = reinterpret_cast<v4f *>(x.p[j]);
+    v4f *__restrict__ vj = reinterpret_cast<v4f *>(v.p[j]);
+    const v4f *__restrict__ gj = reinterpret_cast<const v4f *>(g.p[j]);
+    const unsigned c = rows_column(DASGD_BLOCK_OF_WG, threadIdx.x, rows_head(xj));
+    if (c >= row4) return;
+    v4f a = {0.f, 0.f, 0.f, 0.f};
+    if (MERGE) { a = ld4<false>(A + c); arrived(a); }
+    v4f xr = ld4<true>(xj + c); arrived(xr);
+    v4f vr = ld4<true>(vj + c); arrived(vr);
+    v4f gr = ld4<true>(gj + c); arrived(gr);
     sgd4(xr, vr, gr, lr, momentum, wd);
-    if (WX) st4<true>(x + i, xr);
-    st4<true>(v + i, vr);
-    if (WS) st4<true>(s + i, xr);
+    st4<true>(vj + c, vr);
+    if (WS) st4<true>(S + (int64_t)j * s_stride4 + c, xr);
+    if (WX) st4<true>(xj + c, MERGE ? merge4(xr, a, om) : xr);
 }
 
-// Work decomposition of the matrix-layout kernels that need the column of an element (to read the
-// average A): the flat index space [0, W*row4) of 128-bit elements is cut into aligned blocks of 64
-// (one wavefront, one whole kilobyte per array whatever the row length -- misaligned kilobytes cost
-// 15 % of the bandwidth on MI355X).  A block that holds the boundary between rows j and j+1 belongs
-// to row j and serves both.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2;
-// the blocks of an XCD are issued in bands: B = 2^log_band column windows of row 0, the same windows
-// of row 1, ... of row W-1, then the next band.  The band's piece of A (B KiB per XCD) is fetched from
-// HBM once and re-read from that L2 by the other W-1 rows.  B = 1 issues the W replicas of one
-// window back to back; which B is fastest depends on the row length (the host measures it).
-// Returns false if this workgroup/lane has nothing to do; else the flat index i and the column c.
-// The part of it that does not depend on the lane (also callable on the host, where the tests check
-// that every block of every row is owned exactly once): block index, and the flat range of its row.
-__host__ __device__ __forceinline__ bool decode_owner(unsigned b, unsigned W, unsigned row4, unsigned log_band,
-                                                      unsigned &blk, unsigned &lo, unsigned &hi)
-{
-    const unsigned xcd = b & 7u, slot = b >> 3;
-    const unsigned w = slot & ((1u << log_band) - 1u), t = slot >> log_band;
-    const unsigned j = t % W, band = t / W;
-    const unsigned q = (((band << log_band) + w) << 3) + xcd;    // column window
-    lo = j * row4; hi = lo + row4;                           // flat range of row j
-    const unsigned first = (lo + 63u) >> 6;                  // first block owned by row j
-    const unsigned last = (hi - 1u) >> 6;                    // last one (it may reach into row j+1)
-    blk = first + q;
-    return blk <= last;
-}
-__device__ __forceinline__ bool decode_block(unsigned b, unsigned W, unsigned row4, unsigned n4, unsigned log_band,
-                                             unsigned &i, unsigned &c)
-{
-    unsigned blk, lo, hi;
-    if (!decode_owner(b, W, row4, log_band, blk, lo, hi)) return false;
-    i = blk * kWave + threadIdx.x;
-    if (i >= n4) return false;
-    c = (i >= hi) ? i - hi : i - lo;
-    return true;
-}
-// Largest useful log_band for a row length, and the number of workgroups decode_block needs.
-static inline unsigned decode_windows_per_xcd(unsigned row4)
-{
-    return ((row4 >> 6) + 2u + 7u) / 8u;                     // blocks one row can own (upper bound), per XCD
-}
-static inline unsigned decode_clamp_log_band(unsigned row4, unsigned log_band)
-{
-    while (log_band > 0 && (1u << log_band) > decode_windows_per_xcd(row4)) --log_band;
-    return log_band;
-}
-static inline uint64_t decode_grid(unsigned W, unsigned row4, unsigned log_band)
-{
-    const uint64_t per_xcd = decode_windows_per_xcd(row4), B = 1ull << log_band;
-    return (per_xcd + B - 1) / B * B * 8ull * W;
-}
-
-// Matrix layout, local step with this step's merge folded in (paper Eq. 2, both branches in one
-// pass): y = local update of x;  x <- y + (1 - xi)(A - y);  optionally snapshot <- y.
-// Reads x, v, g once and the average A once (re-reads come from L2); writes x, v [, snapshot]:
-// 20 + 4/W bytes per replica-element (24 + 4/W with the snapshot) instead of the 28 + 4/W (32 + 4/W)
-// of separate local-step and merge kernels.  Needs n4 = W*P/4 < 2^31.
-template <bool SNAP, int WT>   // WT > 0: W known at compile time; 0: any W
+// Delayed merge, rows addressing: x_j <- y_j + (1 - xi)(A - y_j), where y_j is the value after the
+// local step (held in x_j, or in the snapshot when the local step stored only that).  Same grid as the
+// folded step.  (8 + 4/W) bytes per element.
+template <bool FROM_S>
 __global__ void __launch_bounds__(kWave)
-k_step_merge_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, v4f *__restrict__ s,
-                  const v4f *__restrict__ A, unsigned n4, unsigned row4, int W, unsigned log_band,
-                  float lr, float momentum, float wd, float om)
+k_merge_rows(const RowSet x, const v4f *__restrict__ S, int64_t s_stride4, const v4f *__restrict__ A, unsigned row4, float om)
 {
-    unsigned i, c;
-    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, log_band, i, c)) return;
-    v4f xr = ld4<true>(x + i);
-    v4f vr = ld4<true>(v + i);
-    const v4f gr = ld4<true>(g + i);
-    const v4f a = ld4<false>(A + c);
-    sgd4(xr, vr, gr, lr, momentum, wd);
-    st4<true>(v + i, vr);
-    if (SNAP) st4<true>(s + i, xr);
-    st4<true>(x + i, merge4(xr, a, om));
+    const unsigned j = blockIdx.y;
+    v4f *__restrict__ xj = reinterpret_cast<v4f *>(x.p[j]);
+    const unsigned c = rows_column(DASGD_BLOCK_OF_WG, threadIdx.x, rows_head(xj));
+    if (c >= row4) return;
+    v4f a = ld4<false>(A + c); arrived(a);
+    const v4f y = FROM_S ? ld4<true>(S + (int64_t)j * s_stride4 + c) : ld4<true>(xj + c);
+    st4<true>(xj + c, merge4(y, a, om));
 }
 
 // ------------------------------------------------------------------------------------------------
-// Sum of r[LO..HI) in pairwise (tree) order.
+// Sum of r[LO..HI) in pairwise (tree) order: the left part gets the larger half.
 template <int LO, int HI> __device__ __forceinline__ v4f tree_sum(const v4f *r) {
     if constexpr (HI - LO == 1) return r[LO];
     else {
@@ -281,295 +191,163 @@ template <int LO, int HI> __device__ __forceinline__ v4f tree_sum(const v4f *r) 
     }
 }
 
-// W-way replica mean over library-owned rows: A[i] = (1/W) sum_j S[j][i].  One lane owns one
-// 128-bit column and reads it from all W rows (W independent loads in flight), so the reduction
-// needs no cross-lane traffic.  (4 + 4/W) bytes per replica-element.  Single-wave workgroups.  WT > 0: W known at compile
-// time, the whole column set is loaded before the tree sum; WT == 0: any W, four rows at a time.
-template <int WT, int U, bool NT, bool RUNS>
-__global__ void __launch_bounds__(kWave)
-k_mean(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4, int W, float inv_w)
-{
-    // The mean runs beside whatever the caller has on the main stream (typically dense compute that
-    // leaves wave slots free but keeps the issue ports busy): its few instructions go first.
-    __builtin_amdgcn_s_setprio(3);
-    // RUNS: eight consecutive 64-column windows go to the same XCD back to back.  When the rows are
-    // not 128-byte aligned relative to each other, the cache line two neighbouring windows share is
-    // then found in that XCD's L2 instead of being fetched from HBM twice.  Aligned rows share no
-    // lines and keep the plain order, which is a little faster.
-    const int64_t blk = RUNS ? ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7)
-                             : (int64_t)blockIdx.x;
-    const int64_t base = blk * (kWave * U) + threadIdx.x;
-    if constexpr (WT > 0) {
-        v4f r[U][WT];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kWave;
-            if (i < n4) {
-#pragma unroll
-                for (int j = 0; j < WT; ++j) r[u][j] = ld4<NT>(S + (int64_t)j * row4 + i);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kWave;
-            if (i < n4) st4<false>(A + i, tree_sum<0, WT>(r[u]) * inv_w);
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = base + (int64_t)u * kWave;
-            if (i >= n4) continue;
-            v4f acc = {0.f, 0.f, 0.f, 0.f};
-            int j = 0;
-            for (; j + 4 <= W; j += 4) {
-                const v4f a = ld4<NT>(S + (int64_t)(j + 0) * row4 + i);
-                const v4f b = ld4<NT>(S + (int64_t)(j + 1) * row4 + i);
-                const v4f c = ld4<NT>(S + (int64_t)(j + 2) * row4 + i);
-                const v4f d = ld4<NT>(S + (int64_t)(j + 3) * row4 + i);
-                acc += (a + b) + (c + d);
-            }
-            for (; j < W; ++j) acc += ld4<NT>(S + (int64_t)j * row4 + i);
-            st4<false>(A + i, acc * inv_w);
-        }
-    }
+// Column windows of the mean kernels: workgroup b takes the 64-column window mean_window(b).  RUNS:
+// eight consecutive windows go to the same L2 partition back to back (workgroup b runs on partition
+// b mod 8).  When the rows are not 128-byte aligned relative to each other, the cache line two
+// neighbouring windows share is then found in that L2 instead of being fetched from HBM twice.
+// Aligned rows share no lines and keep the plain order, which is a little faster.  A permutation of
+// [0, 64 n) for every n: the grid is rounded up to a multiple of 64 workgroups.
+template <bool RUNS> __host__ __device__ __forceinline__ uint64_t mean_window(uint64_t b) {
+    return RUNS ? ((b >> 6) * 8 + (b & 7)) * 8 + ((b >> 3) & 7) : b;
 }
 
-// The same mean with the rows split over the NW wavefronts of a workgroup and the partial sums
-// staged through LDS: wavefront w sums rows [w*R, (w+1)*R) of a 64-column window (R = W / NW loads
-// in flight per lane), writes its partial to LDS, and after the barrier wavefront 0 adds the NW
-// partials and stores the average.  With few rows per wave many more waves are in flight, which on
-// MI355X is worth 2-6 % over the lane-owns-a-column form for W = 4, 8, 16 (measured: W=4 90 % vs 85 %
-// of peak, W=8 82 % vs 80 %, W=16 80 % vs 76 %).  Tree order over rows is unchanged (identical bits).
+// W-way replica mean: A[c] = (1/W) sum_j row_j[c].  The rows are split over the NW wavefronts of a
+// workgroup: wavefront w sums rows [w R, (w+1) R) of a 64-column window (R = W / NW loads in flight per
+// lane), writes its partial sum to LDS, and after the barrier wavefront 0 adds the NW partials in tree
+// order and stores the average.  With few rows per wave many more waves are in flight, which measured
+// 2-6 % faster than one lane reading all W rows.  Same pairwise order over rows as a plain tree sum.
+// (4 + 4/W) bytes per element.
 template <int WT, int NW, bool RUNS>
 __global__ void __launch_bounds__(kWave * NW)
-k_mean_lds(const v4f *__restrict__ S, v4f *__restrict__ A, int64_t n4, int64_t row4, float inv_w)
+k_mean_rows(const ConstRowSet rows, v4f *__restrict__ A, unsigned row4, float inv_w)
 {
     constexpr int R = WT / NW;
     static_assert(R * NW == WT && R >= 1, "rows must split evenly over the wavefronts");
     __shared__ v4f part[NW][kWave];
+    // The mean runs beside whatever the caller has on the main stream (typically dense compute that
+    // leaves wave slots free but keeps the issue ports busy): its few instructions go first.
     __builtin_amdgcn_s_setprio(3);
-    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
-    const int64_t blk = RUNS ? ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7)
-                             : (int64_t)blockIdx.x;
-    const int64_t i = blk * kWave + l;
-    if (i < n4) {
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), l = threadIdx.x % kWave;
+    const uint64_t c = mean_window<RUNS>(blockIdx.x) * kWave + l;
+    if (c < row4) {
         v4f r[R];
 #pragma unroll
-        for (int j = 0; j < R; ++j) r[j] = ld4<true>(S + (int64_t)(w * R + j) * row4 + i);
+        for (int j = 0; j < R; ++j) r[j] = ld4<true>(reinterpret_cast<const v4f *>(rows.p[w * R + j]) + c);
         part[w][l] = tree_sum<0, R>(r);
     }
     __syncthreads();
-    if (w == 0 && i < n4) {
+    if (w == 0 && c < row4) {
         v4f p[NW];
 #pragma unroll
         for (int k = 0; k < NW; ++k) p[k] = part[k][l];
-        st4<false>(A + i, tree_sum<0, NW>(p) * inv_w);
+        st4<false>(A + c, tree_sum<0, NW>(p) * inv_w);
     }
+}
+
+// The same for any W up to kMaxRows with one lane reading its column from all rows (W independent
+// loads in flight, no cross-lane traffic), in the same pairwise order.
+template <int WT> __device__ __forceinline__ v4f column_sum(const ConstRowSet &rows, uint64_t c) {
+    v4f r[WT];
+#pragma unroll
+    for (int j = 0; j < WT; ++j) r[j] = ld4<true>(reinterpret_cast<const v4f *>(rows.p[j]) + c);
+    return tree_sum<0, WT>(r);
+}
+template <bool RUNS>
+__global__ void __launch_bounds__(kWave)
+k_mean_any(const ConstRowSet rows, v4f *__restrict__ A, unsigned row4, int W, float inv_w)
+{
+    __builtin_amdgcn_s_setprio(3);
+    const uint64_t c = mean_window<RUNS>(blockIdx.x) * kWave + threadIdx.x;
+    if (c >= row4) return;
+    v4f s;
+    switch (W) {
+#define DASGD_CASE(N) case N: s = column_sum<N>(rows, c); break;
+        DASGD_CASE(1) DASGD_CASE(2) DASGD_CASE(3) DASGD_CASE(4) DASGD_CASE(5) DASGD_CASE(6) DASGD_CASE(7) DASGD_CASE(8)
+        DASGD_CASE(9) DASGD_CASE(10) DASGD_CASE(11) DASGD_CASE(12) DASGD_CASE(13) DASGD_CASE(14) DASGD_CASE(15) DASGD_CASE(16)
+        DASGD_CASE(17) DASGD_CASE(18) DASGD_CASE(19) DASGD_CASE(20) DASGD_CASE(21) DASGD_CASE(22) DASGD_CASE(23) DASGD_CASE(24)
+        DASGD_CASE(25) DASGD_CASE(26) DASGD_CASE(27) DASGD_CASE(28) DASGD_CASE(29) DASGD_CASE(30) DASGD_CASE(31) DASGD_CASE(32)
+#undef DASGD_CASE
+    default: return;
+    }
+    st4<false>(A + c, s * inv_w);
+}
+
+// More than kMaxRows replicas: the rows are those of a library-owned snapshot (base + j * stride), summed
+// four at a time.  Not the pairwise order: equal to it only up to rounding.
+__global__ void __launch_bounds__(kWave)
+k_mean_strided(const v4f *__restrict__ S, int64_t stride4, v4f *__restrict__ A, unsigned row4, int W, float inv_w)
+{
+    __builtin_amdgcn_s_setprio(3);
+    const uint64_t c = (uint64_t)blockIdx.x * kWave + threadIdx.x;
+    if (c >= row4) return;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    int j = 0;
+    for (; j + 4 <= W; j += 4) {
+        const v4f a = ld4<true>(S + (int64_t)(j + 0) * stride4 + c);
+        const v4f b = ld4<true>(S + (int64_t)(j + 1) * stride4 + c);
+        const v4f d = ld4<true>(S + (int64_t)(j + 2) * stride4 + c);
+        const v4f e = ld4<true>(S + (int64_t)(j + 3) * stride4 + c);
+        acc += (a + b) + (d + e);
+    }
+    for (; j < W; ++j) acc += ld4<true>(S + (int64_t)j * stride4 + c);
+    st4<false>(A + c, acc * inv_w);
 }
 
 // Zero-copy snapshot with reconstruction.  When a step both launches an average and merges an older
-// one, the folded kernel leaves only the merged weights x' = y + om (A_old - y) = xi y + om A_old in
-// memory.  The average of the y is still recoverable from them, because the merge is affine and the
-// same for every replica:   mean_j y_j = (mean_j x'_j - om A_old) / xi .
-// So the mean kernel reads the live weights (no snapshot was stored) and undoes the merge on the
-// mean.  The subtraction cancels (operands ~|x|, result ~xi |x|), hence fp64 inside: what remains is
-// the fp32 rounding of the x'_j themselves, averaged over W and amplified by 1/xi.  Rows are split
-// over the NW wavefronts as in k_mean_lds (wave w takes rows w, w+NW, ...: any W).
-typedef double v4d __attribute__((ext_vector_type(4)));
-
+// one, the folded kernel leaves only the merged weights x'_j = y_j + om (A_old - y_j) = xi y_j + om A_old
+// in memory.  The average of the y_j is still recoverable from them, because the merge is affine and
+// the same for every replica:   mean_j y_j = (mean_j x'_j - om A_old) / xi .
+// The subtraction cancels (operands ~|x|, result ~ xi |x|), so the mean of the x'_j must not be rounded
+// at the size of x.  The replicas differ by little, hence single precision suffices on differences:
+//     mean_j x'_j = x'_0 + (1/W) sum_j (x'_j - x'_0)            (each difference exact or nearly so)
+//     mean_j y_j  = ( fma(-om, A_old, x'_0) + (1/W) sum_j (x'_j - x'_0) ) / xi
+// where the fma rounds once, at the size of the result.  What remains is the fp32 rounding of the x'_j
+// themselves, averaged over W and amplified by 1/xi.  Wave w takes rows w, w + NW, ... (any W) and
+// keeps its first row as its own reference; wave 0 refers the others' to row 0.
 template <int NW, bool RUNS>
 __global__ void __launch_bounds__(kWave * NW)
-k_mean_reconstruct(const v4f *__restrict__ X, const v4f *__restrict__ A_old, v4f *__restrict__ A_new,
-                   int64_t n4, int64_t row4, int W, double inv_w, double om, double inv_xi)
+k_mean_undo_merge(const ConstRowSet rows, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4, int W,
+                  float inv_w, float om, float inv_xi)
 {
-    __shared__ v4d part[NW][kWave];
+    __shared__ v4f first[NW][kWave], dsum[NW][kWave];
     __builtin_amdgcn_s_setprio(3);
-    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
-    const int64_t blk = RUNS ? ((int64_t)(blockIdx.x >> 6) * 8 + (blockIdx.x & 7)) * 8 + ((blockIdx.x >> 3) & 7)
-                             : (int64_t)blockIdx.x;
-    const int64_t i = blk * kWave + l;
-    v4d acc = {0.0, 0.0, 0.0, 0.0};
-    if (i < n4) {
-        for (int j = w; j < W; j += NW) {
-            const v4f r = ld4<true>(X + (int64_t)j * row4 + i);
-            acc += __builtin_convertvector(r, v4d);
-        }
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), l = threadIdx.x % kWave;
+    const uint64_t c = mean_window<RUNS>(blockIdx.x) * kWave + l;
+    if (c < row4 && w < W) {
+        const v4f r0 = ld4<true>(reinterpret_cast<const v4f *>(rows.p[w]) + c);
+        v4f d = {0.f, 0.f, 0.f, 0.f};
+        for (int j = w + NW; j < W; j += NW) d += ld4<true>(reinterpret_cast<const v4f *>(rows.p[j]) + c) - r0;
+        first[w][l] = r0;
+        dsum[w][l] = d;
     }
-    part[w][l] = acc;
     __syncthreads();
-    if (w == 0 && i < n4) {
-        v4d m = part[0][l];
+    if (w == 0 && c < row4) {
+        const v4f r0 = first[0][l];
+        v4f d = dsum[0][l];
 #pragma unroll
-        for (int k = 1; k < NW; ++k) m += part[k][l];
-        const v4d a = __builtin_convertvector(ld4<false>(A_old + i), v4d);
-        const v4d y = (m * inv_w - om * a) * inv_xi;
-        st4<false>(A_new + i, __builtin_convertvector(y, v4f));
-    }
-}
-
-// Matrix layout, everything of one iteration in ONE pass: a wavefront owns a window of 64 columns of
-// ALL W rows; per lane it updates the W replicas of its column (local step), sums their new values
-// into the average that is launched at this step (MEAN) and folds the average launched d steps ago
-// into them (MERGE).  No snapshot and no separate mean kernel: 20 + 8/W bytes per replica-element
-// for a step that does all three.  The price is row-strided access: unless P is a multiple of 32 the
-// rows are not 128-byte aligned to each other and the kilobytes a wave touches straddle cache lines.
-// Same operations in the same order as k_local_step_flat + k_mean + k_merge_flat (identical bits).
-template <int WT, bool MEAN, bool MERGE>   // WT > 0: W known at compile time (tree sum); 0: any W
-__global__ void __launch_bounds__(kWave)
-k_step_all_flat(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g,
-                const v4f *__restrict__ A_old, v4f *__restrict__ A_new, int64_t row4, int W,
-                float lr, float momentum, float wd, float om, float inv_w)
-{
-    const int64_t c = (int64_t)blockIdx.x * kWave + threadIdx.x;
-    if (c >= row4) return;
-    v4f a = {0.f, 0.f, 0.f, 0.f};
-    if (MERGE) a = ld4<false>(A_old + c);
-    if constexpr (WT > 0) {
-        v4f y[WT];
-        constexpr int JB = WT < 4 ? WT : 4;
-#pragma unroll
-        for (int j0 = 0; j0 < WT; j0 += JB) {
-            v4f vr[JB], gr[JB];
-#pragma unroll
-            for (int j = 0; j < JB; ++j) {
-                const int64_t i = (int64_t)(j0 + j) * row4 + c;
-                y[j0 + j] = ld4<true>(x + i);
-                vr[j] = ld4<true>(v + i);
-                gr[j] = ld4<true>(g + i);
-            }
-#pragma unroll
-            for (int j = 0; j < JB; ++j) {
-                const int64_t i = (int64_t)(j0 + j) * row4 + c;
-                sgd4(y[j0 + j], vr[j], gr[j], lr, momentum, wd);
-                st4<true>(v + i, vr[j]);
-                st4<true>(x + i, MERGE ? merge4(y[j0 + j], a, om) : y[j0 + j]);
-            }
-        }
-        if (MEAN) st4<false>(A_new + c, tree_sum<0, WT>(y) * inv_w);
-    } else {
-        v4f acc = {0.f, 0.f, 0.f, 0.f};
-        int j = 0;
-        for (; j + 4 <= W; j += 4) {
-            v4f y[4], vr[4], gr[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = (int64_t)(j + u) * row4 + c;
-                y[u] = ld4<true>(x + i);
-                vr[u] = ld4<true>(v + i);
-                gr[u] = ld4<true>(g + i);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = (int64_t)(j + u) * row4 + c;
-                sgd4(y[u], vr[u], gr[u], lr, momentum, wd);
-                st4<true>(v + i, vr[u]);
-                st4<true>(x + i, MERGE ? merge4(y[u], a, om) : y[u]);
-            }
-            acc += (y[0] + y[1]) + (y[2] + y[3]);
-        }
-        for (; j < W; ++j) {
-            const int64_t i = (int64_t)j * row4 + c;
-            v4f y = ld4<true>(x + i), vr = ld4<true>(v + i);
-            const v4f gr = ld4<true>(g + i);
-            sgd4(y, vr, gr, lr, momentum, wd);
-            st4<true>(v + i, vr);
-            st4<true>(x + i, MERGE ? merge4(y, a, om) : y);
-            acc += y;
-        }
-        if (MEAN) st4<false>(A_new + c, acc * inv_w);
+        for (int k = 1; k < NW; ++k)
+            if (k < W) d += dsum[k][l] + (float)((W - k + NW - 1) / NW) * (first[k][l] - r0);   // rows of wave k: each = its reference + ...
+        const v4f a = ld4<false>(A_old + c);
+        v4f t;
+        t.x = fmaf(-om, a.x, r0.x); t.y = fmaf(-om, a.y, r0.y); t.z = fmaf(-om, a.z, r0.z); t.w = fmaf(-om, a.w, r0.w);
+        st4<false>(A_new + c, (t + d * inv_w) * inv_xi);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Delayed merge: x_j <- y_j + (1 - xi)(A - y_j) for every replica j, where y_j is the value after the
-// local step (held in x_j, or in the snapshot when the local step stored only that).
-// Table version: grid = chunks; the chunk of A is read once into registers and applied to all W
-// replicas: (8 + 4/W) bytes per replica-element.
-
-// FROM_S: the pre-merge value y is read from snapshot rows Y (row stride P_pad, chunk at foff)
-// instead of from x (the local step stored only the snapshot).
-template <bool FROM_S>
-__global__ void __launch_bounds__(kThreads)
-k_merge(const Chunk *__restrict__ chunks, float *const *__restrict__ xp, const float *__restrict__ A,
-        const float *__restrict__ Y, int64_t P_pad, int n_tensors, int W, float om)
-{
-    const Chunk c = chunks[blockIdx.x];
-    const float *__restrict__ a = A + c.foff;
-    const v4f *a4 = reinterpret_cast<const v4f *>(a);
-    const int tid = threadIdx.x;
-    const int len = c.len;
-    const bool full = (len == kChunk);
-    const bool a_aligned = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
-
-    v4f ar[kUnroll];
-    if (full && a_aligned) {
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) ar[u] = ld4<false>(a4 + tid + u * kThreads);
-    }
-    for (int j = 0; j < W; ++j) {
-        float *x = xp[(int64_t)j * n_tensors + c.tensor] + c.off;
-        const float *y = FROM_S ? Y + (int64_t)j * P_pad + c.foff : x;
-        const bool aligned = a_aligned && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-        if (aligned) {
-            v4f *x4 = reinterpret_cast<v4f *>(x);
-            const v4f *y4 = reinterpret_cast<const v4f *>(y);
-            if (full) {
-                v4f yr[kUnroll];
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) yr[u] = ld4<true>(y4 + tid + u * kThreads);
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) st4<true>(x4 + tid + u * kThreads, merge4(yr[u], ar[u], om));
-            } else {
-                const int n4 = len >> 2;
-                for (int i = tid; i < n4; i += kThreads) x4[i] = merge4(y4[i], a4[i], om);
-                const int e = (n4 << 2) + tid;
-                if (e < len) { const float ys = y[e]; x[e] = fmaf(om, a[e] - ys, ys); }
-            }
-        } else {
-            for (int e = tid; e < len; e += kThreads) { const float ys = y[e]; x[e] = fmaf(om, a[e] - ys, ys); }
-        }
-    }
-}
-
-// Matrix layout merge: X (and Y, the values after the local step: X itself or the snapshot) are W
-// rows of row4 128-bit columns back to back, A is one row.  Same decomposition as the folded kernel.
-// (8 + 4/W) bytes per replica-element.  Needs n4 = W*P/4 < 2^31.
-template <int WT>   // WT > 0: W known at compile time; 0: any W
-__global__ void __launch_bounds__(kWave)
-k_merge_flat(v4f *__restrict__ X, const v4f *__restrict__ Y, const v4f *__restrict__ A,
-             unsigned n4, unsigned row4, int W, unsigned log_band, float om)
-{
-    unsigned i, c;
-    if (!decode_block(blockIdx.x, WT > 0 ? (unsigned)WT : (unsigned)W, row4, n4, log_band, i, c)) return;
-    const v4f a = ld4<false>(A + c);
-    const v4f y = ld4<true>(Y + i);
-    st4<true>(X + i, merge4(y, a, om));
-}
-
-// The same one-pass iteration with the W rows of a 64-column window spread over the W wavefronts of
-// a workgroup: wavefront j does replica j's local step and merge (three loads in flight per lane
-// instead of 3W, W times as many waves), leaves its y in LDS, and after the barrier wavefront 0 adds
-// the W values in tree order and stores the average.  Measured on MI355X 4-5 % faster than the
-// lane-owns-a-column form at W = 8 (0.72 against 0.75-0.78 ms for the ResNet-50-shaped set).  Same
-// operations in the same order (identical bits).  W = WT is a compile-time constant, 2 <= WT <= 16.
+// Everything of one iteration in ONE pass, rows addressing: the W rows of a 64-column window are
+// spread over the W wavefronts of a workgroup.  Wavefront j does replica j's local step and merge
+// (MERGE), leaves its y in LDS, and after the barrier wavefront 0 adds the W values in tree order and
+// stores the average launched at this step.  No snapshot and no separate mean kernel: 20 + 8/W bytes
+// per element for a step that does all three.  Same operations in the same order as the separate
+// kernels (identical bits).  W = WT is a compile-time constant, 2 <= WT <= 16.
 template <int WT, bool MERGE>
 __global__ void __launch_bounds__(kWave * WT)
-k_step_all_rows(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g,
-                const v4f *__restrict__ A_old, v4f *__restrict__ A_new, int64_t row4,
-                float lr, float momentum, float wd, float om, float inv_w)
+k_step_all_rows(const RowSet x, const RowSet v, const ConstRowSet g, const v4f *__restrict__ A_old, v4f *__restrict__ A_new,
+                unsigned row4, float lr, float momentum, float wd, float om, float inv_w)
 {
     __shared__ v4f part[WT][kWave];
-    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
-    const int64_t c = (int64_t)blockIdx.x * kWave + l;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), l = threadIdx.x % kWave;
+    const uint64_t c = (uint64_t)blockIdx.x * kWave + l;
     if (c < row4) {
-        const int64_t i = (int64_t)w * row4 + c;
-        v4f y = ld4<true>(x + i), vr = ld4<true>(v + i);
-        const v4f gr = ld4<true>(g + i);
+        v4f *xj = reinterpret_cast<v4f *>(x.p[w]) + c, *vj = reinterpret_cast<v4f *>(v.p[w]) + c;
+        v4f y = ld4<true>(xj), vr = ld4<true>(vj);
+        const v4f gr = ld4<true>(reinterpret_cast<const v4f *>(g.p[w]) + c);
         v4f a = {0.f, 0.f, 0.f, 0.f};
         if (MERGE) a = ld4<false>(A_old + c);
         sgd4(y, vr, gr, lr, momentum, wd);
-        st4<true>(v + i, vr);
-        st4<true>(x + i, MERGE ? merge4(y, a, om) : y);
+        st4<true>(vj, vr);
+        st4<true>(xj, MERGE ? merge4(y, a, om) : y);
         part[w][l] = y;
     }
     __syncthreads();
@@ -581,6 +359,155 @@ k_step_all_rows(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict_
     }
 }
 
+// The same for any W up to kMaxRows: one lane updates the W replicas of its column one after the other
+// and keeps their new values for the tree sum.
+template <int WT> __device__ __forceinline__ v4f column_step(const RowSet &x, const RowSet &v, const ConstRowSet &g, uint64_t c, bool merge,
+                                                             v4f a, float lr, float momentum, float wd, float om) {
+    v4f y[WT];
+#pragma unroll
+    for (int j = 0; j < WT; ++j) {
+        v4f *xj = reinterpret_cast<v4f *>(x.p[j]) + c, *vj = reinterpret_cast<v4f *>(v.p[j]) + c;
+        v4f vr = ld4<true>(vj);
+        const v4f gr = ld4<true>(reinterpret_cast<const v4f *>(g.p[j]) + c);
+        y[j] = ld4<true>(xj);
+        sgd4(y[j], vr, gr, lr, momentum, wd);
+        st4<true>(vj, vr);
+        st4<true>(xj, merge ? merge4(y[j], a, om) : y[j]);
+    }
+    return tree_sum<0, WT>(y);
+}
+template <bool MERGE>
+__global__ void __launch_bounds__(kWave)
+k_step_all_any(const RowSet x, const RowSet v, const ConstRowSet g, const v4f *__restrict__ A_old, v4f *__restrict__ A_new,
+               unsigned row4, int W, float lr, float momentum, float wd, float om, float inv_w)
+{
+    const uint64_t c = (uint64_t)blockIdx.x * kWave + threadIdx.x;
+    if (c >= row4) return;
+    v4f a = {0.f, 0.f, 0.f, 0.f};
+    if (MERGE) a = ld4<false>(A_old + c);
+    v4f s;
+    switch (W) {
+#define DASGD_CASE(N) case N: s = column_step<N>(x, v, g, c, MERGE, a, lr, momentum, wd, om); break;
+        DASGD_CASE(1) DASGD_CASE(2) DASGD_CASE(3) DASGD_CASE(4) DASGD_CASE(5) DASGD_CASE(6) DASGD_CASE(7) DASGD_CASE(8)
+        DASGD_CASE(9) DASGD_CASE(10) DASGD_CASE(11) DASGD_CASE(12) DASGD_CASE(13) DASGD_CASE(14) DASGD_CASE(15) DASGD_CASE(16)
+        DASGD_CASE(17) DASGD_CASE(18) DASGD_CASE(19) DASGD_CASE(20) DASGD_CASE(21) DASGD_CASE(22) DASGD_CASE(23) DASGD_CASE(24)
+        DASGD_CASE(25) DASGD_CASE(26) DASGD_CASE(27) DASGD_CASE(28) DASGD_CASE(29) DASGD_CASE(30) DASGD_CASE(31) DASGD_CASE(32)
+#undef DASGD_CASE
+    default: return;
+    }
+    st4<false>(A_new + c, s * inv_w);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Records addressing.  grid = (gx, W, gz); workgroup q = z gx + x of replica y handles block q mod 16 of
+// piece q div 16 (a piece shorter than 16 blocks leaves its last workgroups idle).  A block is 256
+// floats: one 128-bit access per lane when the piece's x, v, g (and snapshot / average) addresses are
+// 16-byte aligned, four 32-bit accesses per lane otherwise; up to three floats past the last whole
+// 128-bit element are done by the lane behind it.
+struct Block {
+    gf32 *x, *v;
+    cgf32 *g;
+    gf32 *s;
+    cgf32 *a;
+    unsigned len, first;        // floats in the piece; first float of this block
+    bool live, aligned;
+};
+template <bool WS, bool MERGE>
+__device__ __forceinline__ Block block_of(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slots,
+                                          const float *const *__restrict__ gp, int n_tensors, float *S, int64_t s_stride, const float *A)
+{
+    Block b;
+    b.live = false;
+    const unsigned q = DASGD_BLOCK_OF_WG, j = blockIdx.y;
+    if (q >= slots) return b;
+    const Rec r = recs[(size_t)j * recs_per_row + (q >> kPieceLog)];
+    b.len = r.len;
+    b.first = (q & ((1u << kPieceLog) - 1u)) * 256u;
+    if (b.first >= r.len) return b;
+    b.live = true;
+    b.x = (gf32 *)r.x;
+    b.v = (gf32 *)r.v;
+    b.g = gp ? (cgf32 *)(gp[(size_t)j * n_tensors + r.tensor] + r.goff) : nullptr;
+    b.s = WS ? (gf32 *)(S + (int64_t)j * s_stride + r.aoff) : nullptr;
+    b.a = MERGE ? (cgf32 *)(A + r.aoff) : nullptr;
+    b.aligned = ((reinterpret_cast<uintptr_t>(r.x) | reinterpret_cast<uintptr_t>(r.v) | (uintptr_t)b.g | (uintptr_t)b.s | (uintptr_t)b.a) & 15u) == 0;
+    return b;
+}
+
+template <int MODE, bool MERGE>
+__global__ void __launch_bounds__(kWave)
+k_step_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slots, const float *const *__restrict__ gp, int n_tensors,
+               float *__restrict__ S, int64_t s_stride, const float *__restrict__ A, float lr, float momentum, float wd, float om)
+{
+    constexpr bool WX = (MODE != kStoreS), WS = (MODE != kStoreX);
+    static_assert(!(MERGE && MODE == kStoreS), "a folded merge always stores x");
+    const Block b = block_of<WS, MERGE>(recs, recs_per_row, slots, gp, n_tensors, S, s_stride, A);
+    if (!b.live) return;
+    if (b.aligned) {
+        const unsigned c = b.first / 4 + threadIdx.x, n4 = b.len >> 2;
+        if (c < n4) {
+            v4f a = {0.f, 0.f, 0.f, 0.f};
+            if (MERGE) { a = *((cgv4f *)b.a + c); arrived(a); }
+            v4f xr = gld4((cgv4f *)b.x + c); arrived(xr);
+            v4f vr = gld4((cgv4f *)b.v + c); arrived(vr);
+            v4f gr = gld4((cgv4f *)b.g + c); arrived(gr);
+            sgd4(xr, vr, gr, lr, momentum, wd);
+            gst4((gv4f *)b.v + c, vr);
+            if (WS) gst4((gv4f *)b.s + c, xr);
+            if (WX) gst4((gv4f *)b.x + c, MERGE ? merge4(xr, a, om) : xr);
+        } else if (c == n4) {
+            for (unsigned e = n4 * 4; e < b.len; ++e) {
+                float xs = b.x[e], vs = b.v[e];
+                sgd1(xs, vs, b.g[e], lr, momentum, wd);
+                b.v[e] = vs;
+                if (WS) b.s[e] = xs;
+                if (WX) b.x[e] = MERGE ? merge1(xs, b.a[e], om) : xs;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned e = b.first + k * kWave + threadIdx.x;
+            if (e < b.len) {
+                float xs = b.x[e], vs = b.v[e];
+                sgd1(xs, vs, b.g[e], lr, momentum, wd);
+                b.v[e] = vs;
+                if (WS) b.s[e] = xs;
+                if (WX) b.x[e] = MERGE ? merge1(xs, b.a[e], om) : xs;
+            }
+        }
+    }
+}
+
+// Delayed merge, records addressing.  FROM_S: the value after the local step is read from the snapshot.
+template <bool FROM_S>
+__global__ void __launch_bounds__(kWave)
+k_merge_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slots, const float *__restrict__ S, int64_t s_stride,
+                const float *__restrict__ A, float om)
+{
+    const Block b = block_of<FROM_S, true>(recs, recs_per_row, slots, nullptr, 0, const_cast<float *>(S), s_stride, A);
+    if (!b.live) return;
+    cgf32 *y = FROM_S ? (cgf32 *)b.s : (cgf32 *)b.x;
+    if (b.aligned) {
+        const unsigned c = b.first / 4 + threadIdx.x, n4 = b.len >> 2;
+        if (c < n4) {
+            v4f a = *((cgv4f *)b.a + c); arrived(a);
+            const v4f yr = gld4((cgv4f *)y + c);
+            gst4((gv4f *)b.x + c, merge4(yr, a, om));
+        } else if (c == n4) {
+            for (unsigned e = n4 * 4; e < b.len; ++e) b.x[e] = merge1(y[e], b.a[e], om);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned e = b.first + k * kWave + threadIdx.x;
+            if (e < b.len) b.x[e] = merge1(y[e], b.a[e], om);
+        }
+    }
+}
+
+// Scalar W-way mean over library-owned rows whose width is not a multiple of four floats or whose
+// base is not 16-byte aligned does not occur: library rows are padded and aligned.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads) k_fill_zero(v4f *__restrict__ p, int64_t n4)
 {

@@ -26,7 +26,12 @@ class GpuRun:
     unpadded offsets (so odd-sized tensors make their successors 16-byte misaligned).
     layout "arena_padded": the same with the row stride rounded up to a multiple of 32 floats
     (plus 32 when it already is one, so that there is always padding), padding poisoned with NaN.
+    layout "matrix": what the benchmark allocates: W x ld with ld a multiple of 256 floats (rows on kilobyte
+    boundaries), zero padding.
     layout "separate": every tensor is its own allocation.
+    layout "rows": one allocation per replica and quantity, the tensors back to back inside it; every
+    row starts a different number of 16-byte units behind a kilobyte boundary (and x, v, g differently).
+    layout "rows_g_separate": weights and momentum as in "rows", every gradient tensor its own allocation.
     """
 
     def __init__(self, cfg: Config, layout: str = "arena", schedule: Optional[int] = None,
@@ -46,15 +51,35 @@ class GpuRun:
         n = cfg.params.n_tensors
         with torch.cuda.stream(self.main):
             w0 = wl.init_weights(cfg, self.dev)
-            if layout in ("arena", "arena_padded"):
+            if layout in ("arena", "arena_padded", "matrix"):
                 ld = P if layout == "arena" else (P + 31) // 32 * 32 + (28 if P % 32 == 0 else 0)
+                if layout == "matrix":
+                    ld = (P + 255) // 256 * 256
                 full = [torch.full((W, ld), float("nan"), device=self.dev) for _ in range(3)]
+                self.full = full                   # (the padding must come back untouched)
                 self.x_flat, self.v_flat, self.g_flat = (a[:, :P] for a in full)
                 self.x_flat.copy_(w0.unsqueeze(0).expand(W, P))
                 self.v_flat.zero_()
                 self.g_flat.zero_()
                 view = lambda a: [[a[j, off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
                 self.x, self.v, self.g = view(self.x_flat), view(self.v_flat), view(self.g_flat)
+            elif layout in ("rows", "rows_g_separate"):
+                def rows(skew):                    # W separate buffers; row j starts 4*(skew + 3j) floats into its own
+                    bufs = [torch.full((P + 4 * (skew + 3 * j) + 8,), float("nan"), device=self.dev) for j in range(W)]
+                    return bufs, [b[4 * (skew + 3 * j): 4 * (skew + 3 * j) + P] for j, b in enumerate(bufs)]
+                self.full, rx = rows(1)
+                fv, rv = rows(5)
+                fg, rg = rows(2)
+                self.full = self.full + fv + fg
+                for j in range(W):
+                    rx[j].copy_(w0); rv[j].zero_(); rg[j].zero_()
+                self.x_flat = self.v_flat = self.g_flat = None
+                self.x_rows, self.v_rows, self.g_rows = rx, rv, rg
+                view = lambda r: [[r[j][off[t]:off[t + 1]] for t in range(n)] for j in range(W)]
+                self.x, self.v, self.g = view(rx), view(rv), view(rg)
+                if layout == "rows_g_separate":
+                    self.g_rows = None
+                    self.g = [[torch.zeros(off[t + 1] - off[t], device=self.dev) for t in range(n)] for _ in range(W)]
             elif layout == "separate":
                 self.x_flat = self.v_flat = self.g_flat = None
                 self.x = [[w0[off[t]:off[t + 1]].clone() for t in range(n)] for _ in range(W)]
@@ -83,7 +108,27 @@ class GpuRun:
         return torch.cat([t.reshape(-1) for t in rows[j]])
 
     def x_of(self, j: int) -> torch.Tensor:
-        return self.x_flat[j] if self.x_flat is not None else self._flat(self.x, j)
+        if self.x_flat is not None:
+            return self.x_flat[j]
+        if getattr(self, "x_rows", None) is not None:
+            return self.x_rows[j]
+        return self._flat(self.x, j)
+
+    def padding_untouched(self) -> bool:
+        """Everything the harness allocated around the rows (poisoned with NaN) is still NaN."""
+        self.main.synchronize(); self.side.synchronize()
+        P, W = self.cfg.P, self.cfg.W
+        full = getattr(self, "full", None)
+        if full is None:
+            return True
+        if full[0].dim() == 2:
+            return all(bool(torch.isnan(a[:, P:]).all()) for a in full)
+        ok = True
+        for q, skew in enumerate((1, 5, 2)):
+            for j in range(W):
+                b, lo = full[q * W + j], 4 * (skew + 3 * j)
+                ok = ok and bool(torch.isnan(b[:lo]).all()) and bool(torch.isnan(b[lo + P:]).all())
+        return ok
 
     def fill_gradients(self, k: int) -> None:
         """Write the gradients of iteration k into the g buffers (on the main stream)."""
@@ -98,6 +143,8 @@ class GpuRun:
                 if self.g_flat is not None:
                     if gj.data_ptr() != self.g_flat[j].data_ptr():
                         self.g_flat[j].copy_(gj)
+                elif getattr(self, "g_rows", None) is not None:
+                    self.g_rows[j].copy_(gj)
                 else:
                     off = cfg.params.offsets
                     for t, dst in enumerate(self.g[j]):
@@ -117,7 +164,7 @@ class GpuRun:
 
     def momentum(self) -> np.ndarray:
         self.main.synchronize()
-        rows = [self.v_flat[j] if self.v_flat is not None else self._flat(self.v, j) for j in range(self.cfg.W)]
+        rows = [self.v_flat[j] if self.v_flat is not None else self._flat(self.v, j) for j in range(self.cfg.W)]   # (views: cat copies)
         return torch.stack(rows).cpu().numpy()
 
     def pending_average(self, which: int = 0) -> np.ndarray:
@@ -151,9 +198,11 @@ def run_gpu(cfg: Config, steps: Optional[int] = None, layout: str = "arena", sch
 # ------------------------------------------------------------------------------------------------
 # oracle side
 def run_oracle(cfg: Config, dtype: str = "f64", steps: Optional[int] = None, idx: Optional[torch.Tensor] = None,
-               observer: Optional[Callable] = None, xi: Optional[float] = None) -> np.ndarray:
+               observer: Optional[Callable] = None, xi: Optional[float] = None, gen_device: Optional[str] = None) -> np.ndarray:
     """Run cfg through the CPU oracle (on all coordinates, or only on the coordinates idx: the
-    method is elementwise across coordinates, so a subset evolves exactly as inside the full run)."""
+    method is elementwise across coordinates, so a subset evolves exactly as inside the full run).
+    gen_device: evaluate the seeded input generator there (it gives the same bits on every device) and
+    copy the inputs to the host; the oracle itself always runs on the host."""
     import oracle
     npdt = np.float32 if dtype == "f32" else np.float64
     w0 = wl.init_weights(cfg, "cpu", idx).numpy()
@@ -163,9 +212,21 @@ def run_oracle(cfg: Config, dtype: str = "f64", steps: Optional[int] = None, idx
     sigma = wl.grad_sigma_vector(cfg, "cpu", idx) if cfg.kind == "external" else None
     quad = wl.QuadraticProblem.build(cfg, "cpu", idx) if cfg.kind == "quadratic" else None
 
+    stage = None
+    if gen_device is not None and quad is None:
+        n = cfg.P if idx is None else idx.numel()
+        idx_dev = None if idx is None else idx.to(gen_device)
+        sigma_dev = wl.grad_sigma_vector(cfg, gen_device, idx_dev)
+        stage = torch.empty((cfg.W, n), dtype=torch.float64 if dtype == "f64" else torch.float32,
+                            pin_memory=torch.device(gen_device).type == "cuda")
+
     def grads(k: int, x: np.ndarray) -> np.ndarray:
         if quad is not None:
             return np.stack([quad.grad(torch.from_numpy(x[j]), k, j, idx=idx).numpy() for j in range(cfg.W)])
+        if stage is not None:
+            for j in range(cfg.W):
+                stage[j].copy_(wl.gradient(cfg, k, j, gen_device, idx=idx_dev, sigma=sigma_dev))
+            return stage.numpy()
         return np.stack([wl.gradient(cfg, k, j, "cpu", idx=idx, sigma=sigma).numpy() for j in range(cfg.W)]).astype(npdt)
 
     out = o.run(cfg.steps if steps is None else steps, grads, observer).copy()

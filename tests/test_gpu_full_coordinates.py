@@ -1,0 +1,70 @@
+"""Every coordinate of every replica at full size: the benchmark configurations run through the GPU
+library in the layout the benchmark times, and through the fp64 CPU oracle over ALL coordinates.
+
+The method is elementwise across coordinates (Eq. 2 couples replicas, never coordinates), so the oracle
+is streamed over contiguous coordinate slices, one test case per slice; its inputs come from the seeded
+generator (evaluated on the GPU and copied to the host: it gives the same bits on every device, which
+test_generator_is_bit_identical_on_host_and_device checks), never from the library.
+Bar: max |x_gpu - x_oracle| <= 1e-5 * parameter scale per tensor, every replica, at every checkpoint.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from harness import TOL, GpuRun, max_scaled_error, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+SLICE = {"resnet50_w8": 1 << 23, "resnet50_w16": 1 << 23, "bert_large_w4": 1 << 25}
+CHECKPOINTS = {"resnet50_w8": None, "resnet50_w16": None, "bert_large_w4": "final"}       # None: {1, tau + d, K/2, K}
+
+
+def cases():
+    out = []
+    for name, n in SLICE.items():
+        P = wl.get_config(name).P
+        out += [(name, lo) for lo in range(0, P, n)]
+    return out
+
+
+_gpu = {}       # name -> {step: weights [W, P] on the host}; one configuration at a time
+
+
+def gpu_checkpoints(name):
+    if name not in _gpu:
+        _gpu.clear()
+        cfg = wl.get_config(name)
+        cps = [cfg.steps] if CHECKPOINTS[name] == "final" else sorted({1, cfg.tau + cfg.d, cfg.steps // 2, cfg.steps})
+        run = GpuRun(cfg, layout="matrix", side_threshold=None)     # the library's defaults, as the benchmark runs it
+        snaps = {}
+        for k in range(cfg.steps):
+            run.step()
+            if k + 1 in cps:
+                snaps[k + 1] = run.weights()
+        assert run.padding_untouched()
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+        _gpu[name] = snaps
+    return _gpu[name]
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,lo", cases())
+def test_all_coordinates_at_full_size(name, lo):
+    cfg = wl.get_config(name)
+    snaps = gpu_checkpoints(name)
+    hi = min(cfg.P, lo + SLICE[name])
+    idx = torch.arange(lo, hi, dtype=torch.int64)
+    errs = {}
+
+    def obs(k, o, what):
+        if k + 1 in snaps:
+            errs[k + 1] = max_scaled_error(cfg, snaps[k + 1][:, lo:hi], o.x, idx)
+
+    run_oracle(cfg, "f64", idx=idx, observer=obs, gen_device="cuda:0")
+    print(f"[{name}] coordinates {lo}..{hi}: scaled error " + ", ".join(f"step {k}: {e:.2e}" for k, e in errs.items()), flush=True)
+    assert sorted(errs) == sorted(snaps) and max(errs.values()) <= TOL
+    if hi == cfg.P:
+        _gpu.clear()
