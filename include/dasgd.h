@@ -274,6 +274,20 @@ int dasgd_step(dasgd_ctx *ctx, const float *const *g, int *began, int *merged);
  * EINVAL: null / misaligned pointer or P % 4 != 0.  ESTATE: not bound. */
 int dasgd_gradient_average(dasgd_ctx *ctx, const float *G, float *out);
 
+/* The blocking average in one call, without a context: A = (1/W) sum_j x_j, then x_j <- xi x_j + (1 - xi) A
+ * for every replica -- Local SGD's averaging step (Section 2.3.3; "delay 0" in Section 4.3), for callers who
+ * take their local steps with an optimiser of their own; with xi = 0 every replica becomes the averaged
+ * model that the paper's analysis follows (Section 3.3.1), e.g. before evaluation or a checkpoint.  Two
+ * kernels on `stream` (the W-way mean into the workspace, the merge out of it); returns without waiting.
+ *   x_rows     host array of W device pointers; replica j is the P contiguous floats at x_rows[j]
+ *              (16-byte aligned, P a multiple of 4, W <= 32), updated in place
+ *   workspace  device, 256-byte aligned, at least P floats; holds A afterwards
+ * Same arithmetic as dasgd_average_begin + dasgd_merge with d = 0 (pairwise sum over the replicas).
+ * EINVAL: bad sizes, null / misaligned pointers, rows that overlap each other or the workspace, a row or
+ * the workspace running past its allocation.  ENOMEM: workspace smaller than P floats.  EHIP: a launch
+ * failed (code via dasgd_last_hip_error(NULL)). */
+int dasgd_average_now(int W, int64_t P, float *const *x_rows, float xi, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The paper's guideline for the delay (Section 3.4, Eq. 3: the communication must fit into d local
  * iterations, t_c < d t_p) and for the period (Section 6.4: tau = d + 1): returns the smallest integer
  * d >= 1 with t_c < d * t_p, and tau = d + 1.  t_c: time of one weight averaging (>= 0), t_p: time of
@@ -285,7 +299,8 @@ int dasgd_choose_delay(double t_c, double t_p, int *d, int *tau);
  * pointer may be NULL. */
 int dasgd_query(const dasgd_ctx *ctx, int64_t *step_k, int *n_pending, int *begin_due, int *merge_due);
 
-/* HIP error code of the most recent DASGD_EHIP (0 if none). */
+/* HIP error code of the most recent DASGD_EHIP of this context (0 if none); with ctx == NULL: of the calling
+ * thread's latest context-free call. */
 int dasgd_last_hip_error(const dasgd_ctx *ctx);
 
 /* Wait for both streams, drop pending averages, release events and host state.  NULL is a no-op. */

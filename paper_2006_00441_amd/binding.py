@@ -53,6 +53,7 @@ EXPORTS = {
     "dasgd_merge": (ctypes.c_int, [_vp]),
     "dasgd_step": (ctypes.c_int, [_vp, _pp, _pint, _pint]),
     "dasgd_gradient_average": (ctypes.c_int, [_vp, _vp, _vp]),
+    "dasgd_average_now": (ctypes.c_int, [ctypes.c_int, _i64, _pp, ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "dasgd_choose_delay": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, _pint, _pint]),
     "dasgd_query": (ctypes.c_int, [_vp, _pi64, _pint, _pint, _pint]),
     "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64, _pint]),
@@ -120,6 +121,15 @@ def choose_delay(t_c: float, t_p: float) -> Tuple[int, int]:
     if rc < 0:
         raise DasgdError("dasgd_choose_delay", rc)
     return int(d.value), int(tau.value)
+
+
+def average_now(x_rows: Sequence[int], P: int, xi: float, workspace_ptr: int, workspace_bytes: int, stream: int) -> None:
+    """x_j <- xi x_j + (1 - xi) mean_j x_j over the W rows of P floats at the device pointers x_rows
+    (dasgd_average_now); the mean is left in the workspace."""
+    rc = lib().dasgd_average_now(len(x_rows), int(P), _ptr_array(x_rows), float(xi), ctypes.c_void_p(int(workspace_ptr)),
+                                 int(workspace_bytes), ctypes.c_void_p(int(stream)))
+    if rc < 0:
+        raise DasgdError("dasgd_average_now", rc, lib().dasgd_last_hip_error(None))
 
 
 def device_extent(ptr: int) -> int:

@@ -495,39 +495,79 @@ inline unsigned mean_grid(unsigned row4) { return ((row4 + kWave - 1) / kWave + 
 
 // W-way mean of `row_elems` floats per row (a multiple of 4, rows 16-byte aligned) into A.
 // rows: the W row pointers (W <= kMaxRows); or strided != nullptr: rows at strided + j * stride floats.
-int launch_mean(dasgd_ctx *c, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
+hipError_t launch_mean_of(int W, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
 {
     const unsigned row4 = (unsigned)(row_elems / 4);
     v4f *A4 = reinterpret_cast<v4f *>(A);
-    const float inv_w = 1.0f / (float)c->W;
+    const float inv_w = 1.0f / (float)W;
     ConstRowSet r = {};
     if (rows) r = *rows;
-    else if (c->W <= kMaxRows)
-        for (int j = 0; j < c->W; ++j) r.p[j] = strided + (int64_t)j * stride;
-    if (c->W > kMaxRows) {
+    else if (W <= kMaxRows)
+        for (int j = 0; j < W; ++j) r.p[j] = strided + (int64_t)j * stride;
+    if (W > kMaxRows) {
         hipLaunchKernelGGL(k_mean_strided, dim3((row4 + kWave - 1) / kWave), dim3(kWave), 0, s,
-                           reinterpret_cast<const v4f *>(strided), stride / 4, A4, row4, c->W, inv_w);
-        HIPCHK(c, hipGetLastError());
-        return DASGD_OK;
+                           reinterpret_cast<const v4f *>(strided), stride / 4, A4, row4, W, inv_w);
+        return hipGetLastError();
     }
-    const bool runs = rows_share_lines(r, c->W);
+    const bool runs = rows_share_lines(r, W);
     const dim3 grid(mean_grid(row4));
 #define DASGD_LAUNCH_MEAN(WT, NW)                                                                               \
     do {                                                                                                        \
         if (runs) hipLaunchKernelGGL((k_mean_rows<WT, NW, true>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w);  \
         else      hipLaunchKernelGGL((k_mean_rows<WT, NW, false>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w); \
     } while (0)
-    switch (c->W) {             // rows split over wavefronts + LDS where that measured faster
+    switch (W) {                // rows split over wavefronts + LDS where that measured faster
     case 4:  DASGD_LAUNCH_MEAN(4, 4);  break;
     case 8:  DASGD_LAUNCH_MEAN(8, 4);  break;
     case 16: DASGD_LAUNCH_MEAN(16, 8); break;
     default:
-        if (runs) hipLaunchKernelGGL((k_mean_any<true>), grid, dim3(kWave), 0, s, r, A4, row4, c->W, inv_w);
-        else      hipLaunchKernelGGL((k_mean_any<false>), grid, dim3(kWave), 0, s, r, A4, row4, c->W, inv_w);
+        if (runs) hipLaunchKernelGGL((k_mean_any<true>), grid, dim3(kWave), 0, s, r, A4, row4, W, inv_w);
+        else      hipLaunchKernelGGL((k_mean_any<false>), grid, dim3(kWave), 0, s, r, A4, row4, W, inv_w);
         break;
     }
 #undef DASGD_LAUNCH_MEAN
-    HIPCHK(c, hipGetLastError());
+    return hipGetLastError();
+}
+int launch_mean(dasgd_ctx *c, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
+{
+    HIPCHK(c, launch_mean_of(c->W, s, rows, strided, stride, A, row_elems));
+    return DASGD_OK;
+}
+
+thread_local int g_last_hip = 0;        // HIP error of the latest failed call that has no context
+
+// The blocking average of dasgd_average_now: A <- mean of the rows, rows <- xi row + (1 - xi) A.  Launches
+// two kernels on `s` and allocates nothing.
+int average_now(int W, int64_t P, float *const *x_rows, float xi, float *A, hipStream_t s)
+{
+    if (W < 1 || W > kMaxRows || P < 4 || P % 4 != 0 || P / 4 > (1ll << 31) - 256) return DASGD_EINVAL;
+    if (!x_rows || !A || !(xi >= 0.f && xi <= 1.f)) return DASGD_EINVAL;
+    std::pair<uintptr_t, size_t> iv[kMaxRows + 1];
+    RowSet xr = {};
+    ConstRowSet cr = {};
+    for (int j = 0; j < W; ++j) {
+        if (!x_rows[j] || (reinterpret_cast<uintptr_t>(x_rows[j]) & 15u)) return DASGD_EINVAL;
+        if (!range_ok(x_rows[j], sizeof(float) * (size_t)P)) return DASGD_EINVAL;
+        xr.p[j] = x_rows[j];
+        cr.p[j] = x_rows[j];
+        iv[j] = {reinterpret_cast<uintptr_t>(x_rows[j]), sizeof(float) * (size_t)P};
+    }
+    iv[W] = {reinterpret_cast<uintptr_t>(A), sizeof(float) * (size_t)P};
+    std::sort(iv, iv + W + 1);
+    for (int i = 1; i <= W; ++i)
+        if (iv[i].first < iv[i - 1].first + iv[i - 1].second) return DASGD_EINVAL;     // rows and scratch must not share bytes
+    hipError_t e = launch_mean_of(W, s, &cr, nullptr, 0, A, P);
+    if (e == hipSuccess) {
+        const unsigned row4 = (unsigned)(P / 4);
+        const dim3 grid = band_grid(rows_blocks(row4), W, 9).grid;
+        hipLaunchKernelGGL((k_merge_rows<false>), grid, dim3(kWave), 0, s, xr, static_cast<const v4f *>(nullptr), (int64_t)0,
+                           reinterpret_cast<const v4f *>(A), row4, 1.0f - xi);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        return DASGD_EHIP;
+    }
     return DASGD_OK;
 }
 
@@ -1092,7 +1132,15 @@ int dasgd_query(const dasgd_ctx *c, int64_t *step_k, int *n_pending, int *bdue, 
     return DASGD_OK;
 }
 
-int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : 0; }
+int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : g_last_hip; }
+
+int dasgd_average_now(int W, int64_t P, float *const *x_rows, float xi, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return DASGD_EINVAL;
+    if (P < 1 || workspace_bytes / sizeof(float) < (size_t)P) return DASGD_ENOMEM;
+    if (!range_ok(workspace, sizeof(float) * (size_t)P)) return DASGD_EINVAL;
+    return average_now(W, P, x_rows, xi, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+}
 
 void dasgd_destroy(dasgd_ctx *c)
 {

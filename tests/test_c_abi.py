@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     method, diag = declared_in("dasgd.h"), declared_in("dasgd_diag.h")
     assert {"dasgd_create", "dasgd_bind", "dasgd_local_step", "dasgd_average_begin", "dasgd_merge", "dasgd_destroy",
             "dasgd_set_xi", "dasgd_set_lr", "dasgd_workspace_bytes", "dasgd_query", "dasgd_step"} <= set(method)
-    assert len(method) <= 18, "diagnostics belong in dasgd_diag.h"
+    assert len(method) <= 20, "diagnostics belong in dasgd_diag.h"
     assert not set(method) & set(diag)
     assert {"dasgd_profile", "dasgd_band", "dasgd_check_work_map", "dasgd_bind_dry_run"} <= set(diag)
     names = sorted(method + diag)
