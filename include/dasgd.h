@@ -288,6 +288,17 @@ int dasgd_gradient_average(dasgd_ctx *ctx, const float *G, float *out);
  * failed (code via dasgd_last_hip_error(NULL)). */
 int dasgd_average_now(int W, int64_t P, float *const *x_rows, float xi, void *workspace, size_t workspace_bytes, void *stream);
 
+/* dasgd_average_now for callers that cannot allocate device memory or hand any over -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: the average goes to a scratch array that
+ * is part of the library's device code (128 MiB per GPU, held from the first use of the library on that
+ * GPU until the process ends) instead of a workspace.  The call allocates nothing and calls no allocating
+ * routine; inputs, outputs, arithmetic and errors are those of dasgd_average_now, plus
+ *   ENOMEM  P > 33,554,432 floats (the scratch array's size): use dasgd_average_now with a workspace.
+ * All calls on one GPU share that GPU's scratch array: two calls whose kernels may run at the same time
+ * (different streams, different threads) race; calls on one stream are ordered and safe.  Nothing in the
+ * array needs clearing between calls: each call writes the P floats it then reads. */
+int dasgd_average_now_static(int W, int64_t P, float *const *x_rows, float xi, void *stream);
+
 /* The paper's guideline for the delay (Section 3.4, Eq. 3: the communication must fit into d local
  * iterations, t_c < d t_p) and for the period (Section 6.4: tau = d + 1): returns the smallest integer
  * d >= 1 with t_c < d * t_p, and tau = d + 1.  t_c: time of one weight averaging (>= 0), t_p: time of

@@ -54,6 +54,7 @@ EXPORTS = {
     "dasgd_step": (ctypes.c_int, [_vp, _pp, _pint, _pint]),
     "dasgd_gradient_average": (ctypes.c_int, [_vp, _vp, _vp]),
     "dasgd_average_now": (ctypes.c_int, [ctypes.c_int, _i64, _pp, ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "dasgd_average_now_static": (ctypes.c_int, [ctypes.c_int, _i64, _pp, ctypes.c_float, _vp]),
     "dasgd_choose_delay": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, _pint, _pint]),
     "dasgd_query": (ctypes.c_int, [_vp, _pi64, _pint, _pint, _pint]),
     "dasgd_layout": (ctypes.c_int, [_vp, _pi64, _pi64, _pint]),
@@ -130,6 +131,14 @@ def average_now(x_rows: Sequence[int], P: int, xi: float, workspace_ptr: int, wo
                                  int(workspace_bytes), ctypes.c_void_p(int(stream)))
     if rc < 0:
         raise DasgdError("dasgd_average_now", rc, lib().dasgd_last_hip_error(None))
+
+
+def average_now_static(x_rows: Sequence[int], P: int, xi: float, stream: int) -> None:
+    """dasgd_average_now with the library's own static scratch array in place of a workspace
+    (dasgd_average_now_static): allocates nothing."""
+    rc = lib().dasgd_average_now_static(len(x_rows), int(P), _ptr_array(x_rows), float(xi), ctypes.c_void_p(int(stream)))
+    if rc < 0:
+        raise DasgdError("dasgd_average_now_static", rc, lib().dasgd_last_hip_error(None))
 
 
 def device_extent(ptr: int) -> int:

@@ -11,6 +11,7 @@
 #include <cstring>
 #include <algorithm>
 #include <deque>
+#include <mutex>
 #include <utility>
 #include <new>
 #include <vector>
@@ -535,6 +536,37 @@ int launch_mean(dasgd_ctx *c, hipStream_t s, const ConstRowSet *rows, const floa
 }
 
 thread_local int g_last_hip = 0;        // HIP error of the latest failed call that has no context
+
+// Scratch memory of dasgd_average_now_static: the average of one call.  Every GPU the library runs on holds
+// its own copy of the array, at its own address, until the process ends.  Host code must not use the name
+// as an address: the per-device address comes from hipGetSymbolAddress, once per device.
+constexpr int64_t kStaticScratchFloats = 32ll << 20;        // 128 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+int static_scratch(float **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) return DASGD_EINVAL;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess) g_scratch_ptr[dev] = static_cast<float *>(p);
+        }
+        *out = g_scratch_ptr[dev];
+    }
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        return DASGD_EHIP;
+    }
+    return DASGD_OK;
+}
 
 // The blocking average of dasgd_average_now: A <- mean of the rows, rows <- xi row + (1 - xi) A.  Launches
 // two kernels on `s` and allocates nothing.
@@ -1133,6 +1165,16 @@ int dasgd_query(const dasgd_ctx *c, int64_t *step_k, int *n_pending, int *bdue, 
 }
 
 int dasgd_last_hip_error(const dasgd_ctx *c) { return c ? c->last_hip : g_last_hip; }
+
+int dasgd_average_now_static(int W, int64_t P, float *const *x_rows, float xi, void *stream)
+{
+    if (P < 1) return DASGD_EINVAL;
+    if (P > kStaticScratchFloats) return DASGD_ENOMEM;      // larger replicas: dasgd_average_now with a workspace
+    float *A = nullptr;
+    const int rc = static_scratch(&A);
+    if (rc != DASGD_OK) return rc;
+    return average_now(W, P, x_rows, xi, A, static_cast<hipStream_t>(stream));
+}
 
 int dasgd_average_now(int W, int64_t P, float *const *x_rows, float xi, void *workspace, size_t workspace_bytes, void *stream)
 {
