@@ -556,13 +556,13 @@ def cpu_baseline(cfg, budget_s: float = 12.0):
 
 
 def pmc_traffic(kernel: str, workload: str, layout: str = "matrix"):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
-    tag = "" if layout == "matrix" else f"_{layout}"
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}{tag}_pmc.txt")
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of the default settings on
+    this workload and layout (profiles/step_<workload>_<layout>_pmc.txt), or None."""
+    path = os.path.join(ROOT, "profiles", f"step_{workload}_{layout}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+            if line.startswith(f"traffic_bytes_per_launch {kernel}:"):
+                return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
     return None
@@ -628,6 +628,8 @@ def main() -> int:
     # behind a stand-in of the caller's looks long by the clock without being the one that does the work)
     dom = max(kernels, key=lambda k: kernels[k]["algorithmic_bytes"] * max(kernels[k]["launches"], 1))
     d = kernels[dom]
+    default_settings = args.fusion is None and args.snapshot is None and args.schedule is None and stand_in == "none"
+    traffic = lambda k: pmc_traffic(k, cfg.name, args.layout) if default_settings else None
     out = {
         "metric": "replica-params updated/s + achieved HBM GB/s; % averaging time hidden",
         "value": m["value"],
@@ -643,10 +645,10 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac_of_hbm_peak"], "avg_ms": d["avg_ms"], "launches": d["launches"], "timed_launches": d["timed_launches"],
                      "algorithmic_bytes_per_launch": d["algorithmic_bytes"],
-                     "traffic": pmc_traffic(dom, cfg.name, args.layout)},
+                     "traffic": traffic(dom)},
         "kernels": {n: {"avg_ms": round(k["avg_ms"], 5), "launches": k["launches"], "timed_launches": k["timed_launches"],
                         "GBps": round(k["GBps"], 1), "frac_of_hbm_peak": round(k["frac_of_hbm_peak"], 4),
-                        "traffic": pmc_traffic(n, cfg.name, args.layout)} for n, k in kernels.items()},
+                        "traffic": traffic(n)} for n, k in kernels.items()},
         "tuning": m["tuning"],
         "whole_step": m["whole_step"],
     }

@@ -341,10 +341,11 @@ k_step_all_rows(const RowSet x, const RowSet v, const ConstRowSet g, const v4f *
     const uint64_t c = (uint64_t)blockIdx.x * kWave + l;
     if (c < row4) {
         v4f *xj = reinterpret_cast<v4f *>(x.p[w]) + c, *vj = reinterpret_cast<v4f *>(v.p[w]) + c;
-        v4f y = ld4<true>(xj), vr = ld4<true>(vj);
-        const v4f gr = ld4<true>(reinterpret_cast<const v4f *>(g.p[w]) + c);
         v4f a = {0.f, 0.f, 0.f, 0.f};
-        if (MERGE) a = ld4<false>(A_old + c);
+        if (MERGE) { a = ld4<false>(A_old + c); arrived(a); }
+        v4f y = ld4<true>(xj); arrived(y);
+        v4f vr = ld4<true>(vj); arrived(vr);
+        v4f gr = ld4<true>(reinterpret_cast<const v4f *>(g.p[w]) + c); arrived(gr);
         sgd4(y, vr, gr, lr, momentum, wd);
         st4<true>(vj, vr);
         st4<true>(xj, MERGE ? merge4(y, a, om) : y);
