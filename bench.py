@@ -56,6 +56,7 @@ def algorithmic_bytes_per_rp(kernel: str, W: int) -> float:
 # ------------------------------------------------------------------------------------------------
 # streams
 _hip = None
+_masked_streams = []       # raw handles of the CU-masked streams, destroyed again by destroy_partitioned_streams
 
 
 def cu_partitioned_streams():
@@ -69,6 +70,8 @@ def cu_partitioned_streams():
         _hip = ctypes.CDLL("libamdhip64.so")
         _hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32)]
         _hip.hipExtStreamCreateWithCUMask.restype = ctypes.c_int
+        _hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipStreamDestroy.restype = ctypes.c_int
     side = {i for i in range(256) if i % 8 == i // 32}
     out = []
     for bits in (set(range(256)) - side, side):
@@ -79,8 +82,17 @@ def cu_partitioned_streams():
         rc = _hip.hipExtStreamCreateWithCUMask(ctypes.byref(h), 8, words)
         if rc != 0:
             raise RuntimeError(f"hipExtStreamCreateWithCUMask: {rc}")
+        _masked_streams.append(h.value)
         out.append(torch.cuda.ExternalStream(h.value, device=torch.device("cuda:0")))
     return out[0], out[1], 256 - len(side), len(side)
+
+
+def destroy_partitioned_streams():
+    """Destroy the streams cu_partitioned_streams made (after everything on them has finished)."""
+    import torch
+    torch.cuda.synchronize()
+    while _masked_streams:
+        _hip.hipStreamDestroy(ctypes.c_void_p(_masked_streams.pop()))
 
 
 # ------------------------------------------------------------------------------------------------
@@ -590,6 +602,8 @@ def main() -> int:
     ap.add_argument("--stand-in", default=None, choices=["none", "gemm", "alu"],
                     help="forward/backward stand-in on the main stream before every step of the timed region: "
                          "bf16 8192^3 GEMM (default for --workload overlap), the register-light ALU kernel, or none")
+    ap.add_argument("--cu-partition", action="store_true",
+                    help="run the headline block on CU-partitioned streams (main stream on 224 CUs, side stream on the other 32)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark: xi / d / tau study on the quadratic, one JSON line")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -620,7 +634,11 @@ def main() -> int:
     have_standin = os.path.exists(os.path.join(ROOT, "bench_standin.so"))
 
     # ---- headline -------------------------------------------------------------------------------
-    arena = Arena(cfg, args.layout)
+    streams, stream_note = None, "two default streams"
+    if args.cu_partition:
+        main_s, side_s, n_main, n_side = cu_partitioned_streams()
+        streams, stream_note = (main_s, side_s), f"hipExtStreamCreateWithCUMask: main stream on {n_main} CUs, side stream on the other {n_side}"
+    arena = Arena(cfg, args.layout, streams=streams)
     m = measure(arena, args.steps, args.warmup, stand_in=stand_in, schedule=args.schedule, fusion=args.fusion, snapshot=args.snapshot)
     run = m.pop("_run")
     kernels = m["kernels"]
@@ -628,7 +646,7 @@ def main() -> int:
     # behind a stand-in of the caller's looks long by the clock without being the one that does the work)
     dom = max(kernels, key=lambda k: kernels[k]["algorithmic_bytes"] * max(kernels[k]["launches"], 1))
     d = kernels[dom]
-    default_settings = args.fusion is None and args.snapshot is None and args.schedule is None and stand_in == "none"
+    default_settings = args.fusion is None and args.snapshot is None and args.schedule is None and stand_in == "none" and not args.cu_partition
     traffic = lambda k: pmc_traffic(k, cfg.name, args.layout) if default_settings else None
     out = {
         "metric": "replica-params updated/s + achieved HBM GB/s; % averaging time hidden",
@@ -640,7 +658,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(cfg), "layout": args.layout, "addressing": m["addressing"], "replica_params": rp,
-                   "stand_in": stand_in, "schedule": "measured by the library: " + m["tuning"]["schedule"]
+                   "stand_in": stand_in, "streams": stream_note, "schedule": "measured by the library: " + m["tuning"]["schedule"]
                    if args.schedule is None else m["tuning"]["schedule"]},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac_of_hbm_peak"], "avg_ms": d["avg_ms"], "launches": d["launches"], "timed_launches": d["timed_launches"],
@@ -654,6 +672,8 @@ def main() -> int:
     }
     if args.only_timed:
         run.close(); arena.close()
+        del run, arena, streams
+        destroy_partitioned_streams()
         print(json.dumps(out))
         return 0
     # spread of the step time: five more timings of 50 steps each on the same context
@@ -674,6 +694,9 @@ def main() -> int:
             f3.pop("_run").close()
             out["fusion_all"] = brief(f3)
     arena.close()
+    if args.cu_partition:
+        del arena, streams, main_s, side_s
+        destroy_partitioned_streams()
     if have_standin:
         ceil_gbs = copy_ceiling(1 << 28)
         out["roofline"]["copy_ceiling_GBps"] = round(ceil_gbs, 1)
@@ -721,6 +744,8 @@ def main() -> int:
                     part["streams"] = f"hipExtStreamCreateWithCUMask: main stream on {n_main} CUs, side stream on the other {n_side} (4 per XCD)"
                     out["overlap"]["with_compute_stand_in_cu_partitioned"] = part
                     a.close()
+                    del a, main_s, side_s
+                    destroy_partitioned_streams()
                 except Exception as e:      # the experiment is context; the benchmark does not depend on it
                     out["overlap"]["with_compute_stand_in_cu_partitioned"] = {"error": str(e)}
             if name == "resnet50_w16":
