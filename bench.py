@@ -323,13 +323,16 @@ def measure(arena: Arena, steps: int, warmup: int, cfg=None, stand_in=None, sche
     return out
 
 
-def brief(m):
-    """The part of a measurement that goes into the JSON line beside the headline."""
+def brief(m, workload=None, layout="matrix"):
+    """The part of a measurement that goes into the JSON line beside the headline.  workload: name of the
+    configuration when it ran with the library's defaults (its committed HBM-counter summary then supplies
+    `traffic`, bytes per launch)."""
+    ks = {}
+    for n, k in m["kernels"].items():
+        ks[n] = {"avg_ms": round(k["avg_ms"], 5), "timed_launches": k["timed_launches"], "frac_of_hbm_peak": round(k["frac_of_hbm_peak"], 4),
+                 "algorithmic_bytes": k["algorithmic_bytes"], "traffic": pmc_traffic(n, workload, layout) if workload else None}
     return {"ms_per_step": round(m["ms_per_step"], 5), "value": m["value"], "unit": "replica-params/s", "addressing": m["addressing"],
-            "whole_step_frac_of_hbm_peak": round(m["whole_step"]["frac_of_hbm_peak"], 4),
-            "kernels": {n: {"avg_ms": round(k["avg_ms"], 5), "timed_launches": k["timed_launches"],
-                            "frac_of_hbm_peak": round(k["frac_of_hbm_peak"], 4)} for n, k in m["kernels"].items()},
-            "tuning": m["tuning"]}
+            "whole_step_frac_of_hbm_peak": round(m["whole_step"]["frac_of_hbm_peak"], 4), "kernels": ks, "tuning": m["tuning"]}
 
 
 def copy_ceiling(n_floats: int):
@@ -712,13 +715,13 @@ def main() -> int:
             mm = measure(a, 40, 5)
             mm.pop("_run").close()
             a.close()
-            layouts[cfg.name][lay] = brief(mm)
+            layouts[cfg.name][lay] = brief(mm, cfg.name, lay)
         for name, steps in (("quadratic", 200), ("resnet50_w8", 80), ("resnet50_w16", 240)):
             c = wl.get_config(name)
             a = Arena(c, "matrix")
             mm = measure(a, steps, 10)
             mm.pop("_run").close()
-            configs[name] = dict(brief(mm), workload=describe(c))
+            configs[name] = dict(brief(mm, name), workload=describe(c))
             if name == "resnet50_w8":
                 # overlap stress: the same parameter set, one bf16 8192^3 GEMM before every step
                 oc = wl.get_config("overlap")
@@ -755,7 +758,7 @@ def main() -> int:
                     mm = measure(a, 240, 10)
                     mm.pop("_run").close()
                     a.close()
-                    layouts[name][lay] = brief(mm)
+                    layouts[name][lay] = brief(mm, name, lay)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     out["bench_seconds"] = round(time.perf_counter() - t_start, 1)

@@ -125,10 +125,10 @@ enum {
                                      scales with 1/xi.  The library's own kernels wait for the mean; a
                                      caller whose OWN kernels write x between two steps (clipping,
                                      loading a checkpoint) must first wait for side_stream, or use the
-                                     copy mode.  Taken when: every replica is one contiguous run (see
-                                     dasgd_local_step); schedule OVERLAP, SERIAL or AUTO; fusion level 2;
-                                     and either no merge falls on the step or xi >= 1/8.  Otherwise the
-                                     copy is made */
+                                     copy mode.  Taken when: schedule OVERLAP, SERIAL or AUTO; fusion level 2;
+                                     and either no merge falls on the step or xi >= 1/8 (any memory
+                                     layout: the mean finds the live weights through row pointers or through
+                                     the record table).  Otherwise the copy is made */
     DASGD_SNAPSHOT_AUTO      = 2  /* default: zero-copy for the first 500 min(1, (xi / 0.25)^2) steps of
                                      the context (none for xi < 1/8), stored snapshots from then on, so
                                      that the accuracy statement at the top of this file holds whatever

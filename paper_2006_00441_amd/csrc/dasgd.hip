@@ -803,7 +803,19 @@ static int launch_average(dasgd_ctx *c, int slot, bool *on_side)
     int rec;
     int rc = prof_open(c, c->zc && c->zc_recon ? DASGD_K_MEAN_RECONSTRUCT : DASGD_K_MEAN, s, &rec);
     if (rc != DASGD_OK) return rc;
-    if (c->zc) {
+    if (c->zc && !c->xv_rows) {
+        // the replicas are not rows: the live weights are found through the records
+        const Rec *recs = reinterpret_cast<const Rec *>(c->ws + c->lay.recs);
+        const unsigned slots = (unsigned)((uint64_t)c->lay.n_pieces << kPieceLog);
+        const float om = 1.0f - c->zc_xi, inv_xi = 1.0f / c->zc_xi, inv_w = 1.0f / (float)c->W;
+        if (c->zc_recon)
+            hipLaunchKernelGGL((k_mean_records<true>), dim3(slots), dim3(kWave), 0, s, recs, (unsigned)c->lay.n_pieces, slots, c->W,
+                               avg_ptr(c, c->zc_old_slot), avg_ptr(c, slot), inv_w, om, inv_xi);
+        else
+            hipLaunchKernelGGL((k_mean_records<false>), dim3(slots), dim3(kWave), 0, s, recs, (unsigned)c->lay.n_pieces, slots, c->W,
+                               static_cast<const float *>(nullptr), avg_ptr(c, slot), inv_w, om, inv_xi);
+        HIPCHK(c, hipGetLastError());
+    } else if (c->zc) {
         ConstRowSet rows = {};
         for (int j = 0; j < c->W; ++j) rows.p[j] = c->xr.p[j];
         if (c->zc_recon) {
@@ -886,7 +898,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     // zero-copy snapshot: store none, let the mean read x (see DASGD_SNAPSHOT_*)
     const bool zc_wanted = c->snapshot == DASGD_SNAPSHOT_ZERO_COPY ||
                            (c->snapshot == DASGD_SNAPSHOT_AUTO && k < zero_copy_budget(c->xi));
-    const bool zc = snap && zc_wanted && c->xv_rows && c->fusion == DASGD_FUSE_STEP_MERGE &&
+    const bool zc = snap && zc_wanted && c->fusion == DASGD_FUSE_STEP_MERGE &&
                     (sched == DASGD_SCHED_OVERLAP || sched == DASGD_SCHED_SERIAL) &&
                     (fold ? c->xi >= 0.125f : !merge_follows);
     if (zc) mode = kStoreX;

@@ -507,8 +507,95 @@ k_merge_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned sl
     }
 }
 
-// Scalar W-way mean over library-owned rows whose width is not a multiple of four floats or whose
-// base is not 16-byte aligned does not occur: library rows are padded and aligned.
+// W-way mean of the live weights, records addressing (zero-copy snapshot when the replicas are not rows):
+// workgroup q handles block q mod 16 of piece q div 16, reads that block from every replica's tensor and
+// writes it to the average at the piece's position.  Pairwise order over the replicas for W <= kMaxRows,
+// four at a time above.  UNDO: the weights already hold the merged values; the merge is undone on the mean
+// as in k_mean_undo_merge (differences to replica 0, one fma at the size of the result).
+template <typename T> __device__ __forceinline__ T piece_load(const float *base, unsigned i);
+template <> __device__ __forceinline__ v4f piece_load<v4f>(const float *base, unsigned i) { return gld4((cgv4f *)base + i); }
+template <> __device__ __forceinline__ float piece_load<float>(const float *base, unsigned i) { return ((cgf32 *)base)[i]; }
+
+template <typename T, int LO, int HI>
+__device__ __forceinline__ T piece_tree(const Rec *__restrict__ recs, size_t rpr, unsigned piece, unsigned i) {
+    if constexpr (HI - LO == 1) return piece_load<T>(recs[(size_t)LO * rpr + piece].x, i);
+    else {
+        constexpr int MID = LO + (HI - LO + 1) / 2;
+        return piece_tree<T, LO, MID>(recs, rpr, piece, i) + piece_tree<T, MID, HI>(recs, rpr, piece, i);
+    }
+}
+template <typename T>
+__device__ __forceinline__ T piece_sum(const Rec *__restrict__ recs, size_t rpr, unsigned piece, unsigned i, int W) {
+    switch (W) {
+#define DASGD_CASE(N) case N: return piece_tree<T, 0, N>(recs, rpr, piece, i);
+        DASGD_CASE(1) DASGD_CASE(2) DASGD_CASE(3) DASGD_CASE(4) DASGD_CASE(5) DASGD_CASE(6) DASGD_CASE(7) DASGD_CASE(8)
+        DASGD_CASE(9) DASGD_CASE(10) DASGD_CASE(11) DASGD_CASE(12) DASGD_CASE(13) DASGD_CASE(14) DASGD_CASE(15) DASGD_CASE(16)
+        DASGD_CASE(17) DASGD_CASE(18) DASGD_CASE(19) DASGD_CASE(20) DASGD_CASE(21) DASGD_CASE(22) DASGD_CASE(23) DASGD_CASE(24)
+        DASGD_CASE(25) DASGD_CASE(26) DASGD_CASE(27) DASGD_CASE(28) DASGD_CASE(29) DASGD_CASE(30) DASGD_CASE(31) DASGD_CASE(32)
+#undef DASGD_CASE
+    default: break;
+    }
+    T acc = T(0.f);
+    int j = 0;
+    for (; j + 4 <= W; j += 4) {
+        const T a = piece_load<T>(recs[(size_t)(j + 0) * rpr + piece].x, i), b = piece_load<T>(recs[(size_t)(j + 1) * rpr + piece].x, i);
+        const T d = piece_load<T>(recs[(size_t)(j + 2) * rpr + piece].x, i), e = piece_load<T>(recs[(size_t)(j + 3) * rpr + piece].x, i);
+        acc += (a + b) + (d + e);
+    }
+    for (; j < W; ++j) acc += piece_load<T>(recs[(size_t)j * rpr + piece].x, i);
+    return acc;
+}
+// mean of the y recovered from the merged weights x' (see k_mean_undo_merge), one element of type T
+template <typename T>
+__device__ __forceinline__ T piece_undo(const Rec *__restrict__ recs, size_t rpr, unsigned piece, unsigned i, int W, T a_old,
+                                        float inv_w, float om, float inv_xi) {
+    const T r0 = piece_load<T>(recs[piece].x, i);
+    T d = T(0.f);
+#pragma unroll 4
+    for (int j = 1; j < W; ++j) d += piece_load<T>(recs[(size_t)j * rpr + piece].x, i) - r0;
+    T t;
+    if constexpr (sizeof(T) == sizeof(float)) t = fmaf(-om, a_old, r0);
+    else { t.x = fmaf(-om, a_old.x, r0.x); t.y = fmaf(-om, a_old.y, r0.y); t.z = fmaf(-om, a_old.z, r0.z); t.w = fmaf(-om, a_old.w, r0.w); }
+    return (t + d * inv_w) * inv_xi;
+}
+
+template <bool UNDO>
+__global__ void __launch_bounds__(kWave)
+k_mean_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slots, int W, const float *__restrict__ A_old,
+               float *__restrict__ A_new, float inv_w, float om, float inv_xi)
+{
+    __builtin_amdgcn_s_setprio(3);
+    const unsigned q = blockIdx.x;
+    if (q >= slots) return;
+    const unsigned piece = q >> kPieceLog, first = (q & ((1u << kPieceLog) - 1u)) * 256u;
+    const Rec r0 = recs[piece];
+    if (first >= r0.len) return;
+    const size_t rpr = recs_per_row;
+    gf32 *out = (gf32 *)(A_new + r0.aoff);
+    cgf32 *old = UNDO ? (cgf32 *)(A_old + r0.aoff) : nullptr;
+    uintptr_t bits = (uintptr_t)out | (uintptr_t)old;
+    for (int j = 0; j < W; ++j) bits |= reinterpret_cast<uintptr_t>(recs[(size_t)j * rpr + piece].x);
+    if ((bits & 15u) == 0) {
+        const unsigned c = first / 4 + threadIdx.x, n4 = r0.len >> 2;
+        if (c < n4) {
+            v4f y;
+            if (UNDO) y = piece_undo<v4f>(recs, rpr, piece, c, W, *((cgv4f *)old + c), inv_w, om, inv_xi);
+            else y = piece_sum<v4f>(recs, rpr, piece, c, W) * inv_w;
+            *((gv4f *)out + c) = y;
+        } else if (c == n4) {
+            for (unsigned e = n4 * 4; e < r0.len; ++e)
+                out[e] = UNDO ? piece_undo<float>(recs, rpr, piece, e, W, old[e], inv_w, om, inv_xi) : piece_sum<float>(recs, rpr, piece, e, W) * inv_w;
+        }
+    } else {
+#pragma unroll 1
+        for (int k = 0; k < 4; ++k) {
+            const unsigned e = first + k * kWave + threadIdx.x;
+            if (e < r0.len)
+                out[e] = UNDO ? piece_undo<float>(recs, rpr, piece, e, W, old[e], inv_w, om, inv_xi) : piece_sum<float>(recs, rpr, piece, e, W) * inv_w;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads) k_fill_zero(v4f *__restrict__ p, int64_t n4)
 {

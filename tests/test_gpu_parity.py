@@ -396,7 +396,7 @@ def test_profile_counts_and_times_launches():
 @pytest.mark.parametrize("tau,d,W,xi", [(1, 1, 4, 0.25), (1, 2, 8, 0.25), (1, 4, 4, 0.5), (2, 2, 3, 0.125), (2, 4, 16, 0.25),
                                         (1, 2, 5, 0.9), (1, 3, 1, 0.25), (1, 2, 8, 1.0)])
 @pytest.mark.parametrize("layout,pset", [("arena", "matrix"), ("arena_padded", "table"), ("arena_padded", "matrix_even"), ("rows", "matrix"),
-                                         ("rows_g_separate", "matrix")])
+                                         ("rows_g_separate", "matrix"), ("separate", "matrix"), ("separate", "table"), ("arena", "table")])
 def test_zero_copy_snapshot_with_reconstruction(tau, d, W, xi, layout, pset):
     """Steps that launch an average and merge an older one at once (d a multiple of tau): no snapshot
     is stored, the mean of the y is recovered from the merged weights.  Rounding differs from the
@@ -408,11 +408,9 @@ def test_zero_copy_snapshot_with_reconstruction(tau, d, W, xi, layout, pset):
     for _ in range(cfg.steps):
         run.step()
     x = run.weights()
-    if run.opt.addressing() != pkg.ADDR_RECORDS:        # replicas are rows: the path under test really ran
-        assert run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2] > 0
-        assert run.opt.profile_read(pkg.K_LOCAL_STEP_SNAP)[2] == 0 and run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] == 0
-    else:
-        assert pset == "table"                          # a replica of odd length cannot be a row of 128-bit columns
+    assert run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2] > 0          # the path under test really ran
+    assert run.opt.profile_read(pkg.K_LOCAL_STEP_SNAP)[2] == 0 and run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] == 0
+    assert (run.opt.addressing() == pkg.ADDR_RECORDS) == (pset == "table" or layout == "separate")   # rows, or through the records
     assert run.padding_untouched()
     run.close()
     both_oracles(cfg, x)
@@ -426,6 +424,9 @@ def test_zero_copy_snapshot_is_exact_without_coinciding_merge(tau, d, W):
     import paper_2006_00441_amd as pkg
     cfg = small(tau=tau, d=d, W=W, steps=4 * tau + d + 3, params=custom_param_set(SETS["matrix"]))
     assert np.array_equal(run_gpu(cfg), run_gpu(cfg, snapshot=pkg.SNAPSHOT_COPY))
+    assert np.array_equal(run_gpu(cfg, layout="separate"), run_gpu(cfg, layout="separate", snapshot=pkg.SNAPSHOT_COPY))
+    ragged = small(tau=tau, d=d, W=W, steps=4 * tau + d + 3, params=custom_param_set(SETS["table"]))
+    assert np.array_equal(run_gpu(ragged), run_gpu(ragged, snapshot=pkg.SNAPSHOT_COPY))
 
 
 def test_zero_copy_falls_back_to_the_copy_for_small_xi():
