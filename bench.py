@@ -377,10 +377,11 @@ def overlap_study(arena: Arena, steps: int, warmup: int, stand_in, label: str):
     stream, F = S0 without snapshot and mean (timing floor).  hidden = (T(S0)-T(S1)) / (T(S0)-T(F))."""
     pkg = arena.pkg
     t = {}
-    for name, sched, snap in (("S0_serial", pkg.SCHED_SERIAL, None), ("S1_overlap", pkg.SCHED_OVERLAP, None),
-                              ("S1_overlap_free_copy_snapshot", pkg.SCHED_OVERLAP_FREE, pkg.SNAPSHOT_COPY),
-                              ("F_no_average", pkg.SCHED_NO_AVERAGE_TIMING_ONLY, None)):
-        r = arena.context(schedule=sched, snapshot=snap, stand_in=stand_in)
+    for name, sched, snap, fusion in (("S0_serial", pkg.SCHED_SERIAL, None, None), ("S1_overlap", pkg.SCHED_OVERLAP, None, None),
+                                      ("S1_overlap_free_copy_snapshot", pkg.SCHED_OVERLAP_FREE, pkg.SNAPSHOT_COPY, None),
+                                      ("F_no_average", pkg.SCHED_NO_AVERAGE_TIMING_ONLY, None, None),
+                                      ("mean_folded_into_the_step_kernel", pkg.SCHED_SERIAL, None, pkg.FUSE_ALL)):
+        r = arena.context(schedule=sched, snapshot=snap, fusion=fusion, stand_in=stand_in)
         t[name] = best_of(r, steps, warmup)
         r.close()
     r = arena.context(stand_in=stand_in)             # what the default (measuring) schedule settles on
@@ -394,6 +395,7 @@ def overlap_study(arena: Arena, steps: int, warmup: int, stand_in, label: str):
     frac = lambda s1: None if t_avg <= 0 else round((t["S0_serial"] - s1) / t_avg, 4)
     return {"stand_in": label, "ms_per_step": {k: round(v, 4) for k, v in t.items()}, "averaging_ms": round(t_avg, 4),
             "hidden_frac": frac(t["S1_overlap"]), "hidden_frac_overlap_free": frac(t["S1_overlap_free_copy_snapshot"]),
+            "removed_frac_by_folding_the_mean_in": frac(t["mean_folded_into_the_step_kernel"]),   # fusion level 3: not hidden, made cheaper
             "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4), "auto_schedule_chose": auto}
 
 
