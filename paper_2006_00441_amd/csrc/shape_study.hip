@@ -573,6 +573,62 @@ __global__ void __launch_bounds__(64 * NW) mean_undo(const RowPtrs p, const v4f 
     }
 }
 
+// ---- local step, mean and merge in one pass (fusion level 3): who walks the W rows of a column window --------
+// one wave walks all W rows of its 64-column window, row after row (TOGETHER: the three loads of a row at once)
+template <int WT, bool TOGETHER>
+__global__ void __launch_bounds__(64) all_walk(const RowPtrs p, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4,
+                                               float lr, float mo, float wd, float om, float inv_w)
+{
+    const unsigned c = blockIdx.x * 64 + threadIdx.x;
+    if (c >= row4) return;
+    v4f a = ld4<false>(A_old + c); arrived(a);
+    v4f y[WT];
+#pragma unroll
+    for (int j = 0; j < WT; ++j) {
+        v4f xr, vr, gr;
+        if (TOGETHER) { xr = ld4<true>(p.x[j] + c); vr = ld4<true>(p.v[j] + c); gr = ld4<true>(p.g[j] + c); arrived(xr, vr, gr); }
+        else { xr = ld4<true>(p.x[j] + c); arrived(xr); vr = ld4<true>(p.v[j] + c); arrived(vr); gr = ld4<true>(p.g[j] + c); arrived(gr); }
+        sgd4(xr, vr, gr, lr, mo, wd);
+        st4<true>(p.v[j] + c, vr);
+        st4<true>(p.x[j] + c, merge4(xr, a, om));
+        y[j] = xr;
+    }
+    st4<false>(A_new + c, tree_sum<0, WT>(y) * inv_w);
+}
+// NW waves per workgroup, each walks WT / NW rows; partial sums through LDS
+template <int WT, int NW>
+__global__ void __launch_bounds__(64 * NW) all_groups(const RowPtrs p, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4,
+                                                      float lr, float mo, float wd, float om, float inv_w)
+{
+    constexpr int R = WT / NW;
+    __shared__ v4f part[NW][64];
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
+    const unsigned c = blockIdx.x * 64 + l;
+    if (c < row4) {
+        v4f a = ld4<false>(A_old + c); arrived(a);
+        v4f y[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const int j = w * R + k;
+            v4f xr = ld4<true>(p.x[j] + c); arrived(xr);
+            v4f vr = ld4<true>(p.v[j] + c); arrived(vr);
+            v4f gr = ld4<true>(p.g[j] + c); arrived(gr);
+            sgd4(xr, vr, gr, lr, mo, wd);
+            st4<true>(p.v[j] + c, vr);
+            st4<true>(p.x[j] + c, merge4(xr, a, om));
+            y[k] = xr;
+        }
+        part[w][l] = tree_sum<0, R>(y);
+    }
+    __syncthreads();
+    if (w == 0 && c < row4) {
+        v4f q[NW];
+#pragma unroll
+        for (int k = 0; k < NW; ++k) q[k] = part[k][l];
+        st4<false>(A_new + c, tree_sum<0, NW>(q) * inv_w);
+    }
+}
+
 __global__ void k_fill(float *p, size_t n, unsigned seed, float scale)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -869,6 +925,21 @@ int main(int argc, char **argv)
                                    lr, mo, wd, (const float *)A, om, W, n_chunks, xo); });
         }
 
+
+        printf("-- pass %d: local step, mean and merge in one pass (20 + 8/W B per replica-parameter), rows into flat\n", rep + 1);
+        {
+            const double B_ALL = 20.0 + 8.0 / W;
+            RowSet ax = {}, av = {}; ConstRowSet ag = {};
+            for (int j = 0; j < W; ++j) { ax.p[j] = (float *)into_flat.x[j]; av.p[j] = (float *)into_flat.v[j]; ag.p[j] = (const float *)into_flat.g[j]; }
+#define ALL_VARIANTS(WT)                                                                                                                          \
+            run("library kernel: W waves per workgroup, one row each, LDS", B_ALL, [&] { hipLaunchKernelGGL((k_step_all_rows<WT, true>), dim3(bpr), dim3(64 * WT), 0, 0, ax, av, ag, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("one wave walks the W rows, a row's loads one after the other", B_ALL, [&] { hipLaunchKernelGGL((all_walk<WT, false>), dim3(bpr), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("one wave walks the W rows, a row's loads together", B_ALL, [&] { hipLaunchKernelGGL((all_walk<WT, true>), dim3(bpr), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("2 waves per workgroup, W/2 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 2>), dim3(bpr), dim3(128), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("4 waves per workgroup, W/4 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 4>), dim3(bpr), dim3(256), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); });
+            switch (W) { case 4: { ALL_VARIANTS(4) } break; case 8: { ALL_VARIANTS(8) } break; default: { ALL_VARIANTS(16) } break; }
+#undef ALL_VARIANTS
+        }
         printf("-- pass %d: W-way mean (4 + 4/W B per replica-parameter)\n", rep + 1);
         run("flat (rows over wavefronts, LDS)", B_MEAN, [&] {
             const unsigned grid = (bpr + 63) / 64 * 64;
