@@ -80,7 +80,8 @@ enum {
                                 nothing, or beside a kernel that fills every SIMD (one large GEMM), the
                                 two cross-stream hand-overs per step only cost time (measured on MI355X:
                                 1-2 % of the step).  After a warm-up of 16 steps (rounded to whole
-                                averaging periods, like the phases) the library alternates the two
+                                averaging periods, like the phases; longer while band lengths are still
+                                being measured, see dasgd_diag.h) the library alternates the two
                                 schedules in six phases of 8 steps, marks the phase boundaries with
                                 events on main_stream -- so the caller's own work is inside the
                                 measurement -- and keeps the schedule with the smaller total once the

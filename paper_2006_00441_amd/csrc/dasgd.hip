@@ -452,7 +452,17 @@ int schedule_tick(dasgd_ctx *c)
             if (!t.ev[i]) { HIPCHK(c, hipEventCreate(&t.ev[i])); t.n_ev = i + 1; }
             HIPCHK(c, hipEventRecord(t.ev[i], c->main_s));
         }
-        if (++t.steps_in_phase >= (t.phase == 0 ? 2 : 1) * t.phase_len) {   // (the warm-up also covers the band trials)
+        ++t.steps_in_phase;
+        bool over = t.steps_in_phase >= t.phase_len;
+        if (t.phase == 0) {
+            // the warm-up lasts two phases and as long as band lengths are still being tried (their timing
+            // events and slower candidates would fall into some phases and not others), within reason
+            bool bands_busy = false;
+            for (const BandTuner &b : c->tuner) bands_busy = bands_busy || (b.n_cand > 0 && b.chosen < 0);
+            over = t.steps_in_phase >= 2 * t.phase_len && t.steps_in_phase % t.phase_len == 0 &&
+                   (!bands_busy || t.steps_in_phase >= 32 * t.phase_len);
+        }
+        if (over) {
             t.steps_in_phase = 0;
             t.phase += 1;
         }
