@@ -84,7 +84,9 @@ enum {
                                 being measured, see dasgd_diag.h) the library alternates the two
                                 schedules in six phases of 8 steps, marks the phase boundaries with
                                 events on main_stream -- so the caller's own work is inside the
-                                measurement -- and keeps the schedule with the smaller total once the
+                                measurement; each mark is recorded after main_stream has been made to
+                                wait for the means still on the side stream, so that a mean counts in
+                                the phase that launched it -- and keeps the schedule with the smaller total once the
                                 marks have completed (seen by a non-blocking query at a later step).
                                 Results do not depend on the choice.  A caller that captures the step
                                 calls into a HIP graph sets a fixed schedule first (event queries are

@@ -441,16 +441,20 @@ int band_close(dasgd_ctx *c, BandTuner &t, int trial)
     return DASGD_OK;
 }
 
-// DASGD_SCHED_AUTO: mark phase boundaries on the main stream, and decide when the marks have completed.
-int schedule_tick(dasgd_ctx *c)
+// DASGD_SCHED_AUTO: one call per local step.  Advances the phases, decides once the marks have completed, and
+// returns in *mark the event (or null) that this step must record on the main stream -- AFTER it has made the
+// main stream wait for the means still running on the side stream, so that a mean is charged to the phase
+// that launched it and not to the next one.
+int schedule_tick(dasgd_ctx *c, hipEvent_t *mark)
 {
+    *mark = nullptr;
     ScheduleTuner &t = c->sched_tuner;
     if (c->schedule != DASGD_SCHED_AUTO || t.chosen >= 0) return DASGD_OK;
     if (t.phase < ScheduleTuner::kPhases) {
         if (t.steps_in_phase == 0 && t.phase >= 1) {            // boundary: start of a measured phase
             const int i = t.phase - 1;
             if (!t.ev[i]) { HIPCHK(c, hipEventCreate(&t.ev[i])); t.n_ev = i + 1; }
-            HIPCHK(c, hipEventRecord(t.ev[i], c->main_s));
+            *mark = t.ev[i];
         }
         ++t.steps_in_phase;
         bool over = t.steps_in_phase >= t.phase_len;
@@ -472,7 +476,7 @@ int schedule_tick(dasgd_ctx *c)
     if (!t.ev[last]) {
         HIPCHK(c, hipEventCreate(&t.ev[last]));
         t.n_ev = last + 1;
-        HIPCHK(c, hipEventRecord(t.ev[last], c->main_s));
+        *mark = t.ev[last];
         return DASGD_OK;
     }
     const hipError_t q = hipEventQuery(t.ev[last]);
@@ -915,7 +919,8 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     bool all = false;               // everything in one kernel?
 
     if (!c->dry) {
-        int rc = schedule_tick(c);
+        hipEvent_t phase_mark = nullptr;
+        int rc = schedule_tick(c, &phase_mark);
         if (rc != DASGD_OK) return rc;
         if (g_changed) {
             // retire the table in use (all kernels reading it are already enqueued), take the next
@@ -946,6 +951,7 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
             HIPCHK(c, hipStreamWaitEvent(c->main_s, c->avg_done[pe.slot], 0));
             pe.awaited = true;
         }
+        if (phase_mark) HIPCHK(c, hipEventRecord(phase_mark, c->main_s));
         if (fold) A = avg_ptr(c, c->pending.front().slot);
         const bool row_kernels = c->xv_rows && g_rows_new;
         all = c->fusion == DASGD_FUSE_ALL && c->d > 0 && row_kernels && snap;
