@@ -227,6 +227,13 @@ class Run:
             extra += 1
         self.torch.cuda.synchronize()
         prev = None
+        # The device queue must never run empty here: a mean on the side stream hides behind what is
+        # enqueued after it, and a host that waits for the device every few steps would take that away
+        # from the overlap phases of the library's schedule measurement.  So the host only stays a few
+        # steps ahead of the device (a training loop does the same when it reads a loss now and then).
+        ahead = 4
+        ring = [self.torch.cuda.Event() for _ in range(ahead)]
+        issued = 0
         while extra < limit:
             now = {k: self.opt.band_state(k)[1:] for k in self.pkg.KERNEL_NAMES}
             # a kind that is neither settled nor issuing trials any more is simply not launched here
@@ -236,9 +243,13 @@ class Run:
                 break
             prev = now
             for _ in range(2 * self.cfg.tau):
+                if issued >= ahead:
+                    ring[issued % ahead].synchronize()
                 self.step()
+                ring[issued % ahead].record(self.arena.main)
+                issued += 1
             extra += 2 * self.cfg.tau
-            self.torch.cuda.synchronize()
+        self.torch.cuda.synchronize()
         return extra
 
     def timed(self, steps: int):
@@ -262,7 +273,8 @@ class Run:
         out = {"schedule": names[sched], "log2_band": {name: self.opt.band(k)[0] for k, name in pkg.KERNEL_NAMES.items()
                                                        if self.opt.band_state(k)[2]}}
         if t_o > 0 and t_s > 0:
-            out["schedule_trial_ms"] = {"overlap": round(t_o, 3), "serial": round(t_s, 3)}
+            out["schedule_trial_ms"] = {"overlap": round(t_o, 3), "serial": round(t_s, 3),
+                                        "phases": [round(v, 3) for v in self.opt.schedule_trial()]}
         return out
 
     def close(self):
@@ -388,7 +400,8 @@ def overlap_study(arena: Arena, steps: int, warmup: int, stand_in, label: str):
     for _ in range(warmup):
         r.step()
     r.settle()
-    auto = r.tuned()["schedule"]
+    tuned = r.tuned()
+    auto = tuned["schedule"]
     t["default_auto"] = best_of(r, steps, 2)
     r.close()
     t_avg = t["S0_serial"] - t["F_no_average"]
@@ -396,7 +409,8 @@ def overlap_study(arena: Arena, steps: int, warmup: int, stand_in, label: str):
     return {"stand_in": label, "ms_per_step": {k: round(v, 4) for k, v in t.items()}, "averaging_ms": round(t_avg, 4),
             "hidden_frac": frac(t["S1_overlap"]), "hidden_frac_overlap_free": frac(t["S1_overlap_free_copy_snapshot"]),
             "removed_frac_by_folding_the_mean_in": frac(t["mean_folded_into_the_step_kernel"]),   # fusion level 3: not hidden, made cheaper
-            "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4), "auto_schedule_chose": auto}
+            "speedup_S0_over_S1": round(t["S0_serial"] / t["S1_overlap"], 4), "auto_schedule_chose": auto,
+            "auto_schedule_trial_ms": tuned.get("schedule_trial_ms")}
 
 
 def compare_algorithms(arena: Arena, steps: int, warmup: int):

@@ -40,6 +40,16 @@ int dasgd_bind_dry_run(dasgd_ctx *ctx, int n_tensors, const int64_t *numel);
  * ESTATE while averages are pending or an average is due. */
 int dasgd_set_side_stream_threshold(dasgd_ctx *ctx, size_t bytes);
 
+/* A mean that goes to the side stream is held back by about `microseconds` (a one-wavefront kernel in
+ * front of it that watches the constant clock), so that the kernel the caller enqueued on main_stream
+ * behind the local step is dispatched first.  The order decides how the two share the chip: a kernel
+ * already in place keeps its wave slots and the mean fills the rest; a mean dispatched first takes every
+ * slot it can use and the caller's kernel starts only as the mean drains (measured on MI355X: a 0.75 ms
+ * kernel took 0.96-1.08 ms behind a 0.16 ms mean that won the race by 0.3 us).  Without it the order is
+ * a race that depends on how far the host runs ahead.  Default 20; 0 = none; at most 200 (EINVAL above).
+ * Results do not depend on it.  May be changed at any time. */
+int dasgd_set_side_stream_head_start(dasgd_ctx *ctx, unsigned microseconds);
+
 /* Layout of the library-owned buffers inside the workspace and the addressing chosen at bind:
  * flat_offset[t] (may be NULL) = element offset of tensor t in a snapshot row / an average;
  * *P_padded = floats per such row: P rounded up to 256 when the replicas are rows (a snapshot row
@@ -91,6 +101,10 @@ int dasgd_band(dasgd_ctx *ctx, int kernel, int *log_band, int *settled, int *tri
  * *overlap_ms / *serial_ms = the measured totals of the three phases each (0 until settled).  Never
  * waits.  Any output pointer may be NULL. */
 int dasgd_schedule_in_use(const dasgd_ctx *ctx, int *schedule, int *settled, double *overlap_ms, double *serial_ms);
+
+/* The six measured phases of DASGD_SCHED_AUTO in the order they ran (OVERLAP, SERIAL, OVERLAP, ...),
+ * milliseconds each, written to phase_ms[0..5]; zeros until the measurement has settled. */
+int dasgd_schedule_trial(const dasgd_ctx *ctx, float *phase_ms);
 
 /* The extent check of dasgd_bind, for callers and tests: *bytes_to_end = number of bytes from p to the
  * end of the device allocation that holds it, as the HIP runtime knows it (a framework's caching

@@ -66,6 +66,8 @@ EXPORTS = {
     "dasgd_device_extent": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
     "dasgd_check_work_map": (ctypes.c_int, [ctypes.c_int, _i64, ctypes.c_int, ctypes.c_int]),
     "dasgd_schedule_in_use": (ctypes.c_int, [_vp, _pint, _pint, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
+    "dasgd_set_side_stream_head_start": (ctypes.c_int, [_vp, ctypes.c_uint]),
+    "dasgd_schedule_trial": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "dasgd_last_hip_error": (ctypes.c_int, [_vp]),
     "dasgd_destroy": (None, [_vp]),
 }
@@ -273,6 +275,12 @@ class DaSGD:
                                                                              ctypes.byref(a), ctypes.byref(b)))
         return int(sc.value), bool(st.value), float(a.value), float(b.value)
 
+    def schedule_trial(self) -> Tuple[float, ...]:
+        """ms of the six measured phases of SCHED_AUTO (overlap, serial, overlap, ...); zeros until settled"""
+        ms = (ctypes.c_float * 6)()
+        self._check("dasgd_schedule_trial", self._lib.dasgd_schedule_trial(self._h, ms))
+        return tuple(float(v) for v in ms)
+
     def pending_average(self, which: int = 0) -> Tuple[int, int]:
         """(launch step, byte offset into the workspace) of pending average `which` (0 = oldest)"""
         ls = ctypes.c_int64(); bo = ctypes.c_size_t()
@@ -295,6 +303,11 @@ class DaSGD:
     def set_side_stream_threshold(self, nbytes: int) -> None:
         """Means smaller than this stay on the main stream even in the overlap schedules (0: none do)."""
         self._check("dasgd_set_side_stream_threshold", self._lib.dasgd_set_side_stream_threshold(self._h, int(nbytes)))
+
+    def set_side_stream_head_start(self, microseconds: int) -> None:
+        """Hold a side-stream mean back by this long so that the caller's next kernel is dispatched first (0: not)."""
+        self._check("dasgd_set_side_stream_head_start",
+                    self._lib.dasgd_set_side_stream_head_start(self._h, int(microseconds)))
 
     def set_band(self, log_band: int) -> None:
         """-1: measure the band length in place (default); 0..11: fix it."""

@@ -71,6 +71,7 @@ struct ScheduleTuner {
     hipEvent_t ev[kPhases + 1] = {};
     int n_ev = 0;
     double overlap_ms = 0, serial_ms = 0;
+    float phase_ms[kPhases - 1] = {};           // measured phases 1..6 in order, once decided
 };
 
 struct Layout {                     // byte offsets into the workspace
@@ -92,6 +93,7 @@ struct dasgd_ctx {
     int snapshot = DASGD_SNAPSHOT_AUTO;
     int slots = 1;
     size_t side_min_bytes = (size_t)64 << 20;   // means that move less than this run on the main stream
+    unsigned head_start_us = 20;                // a side-stream mean is held back by this much (k_head_start)
     // binding
     bool bound = false, dry = false;
     int n_tensors = 0;
@@ -490,6 +492,7 @@ int schedule_tick(dasgd_ctx *c, hipEvent_t *mark)
         float ms = 0.f;
         HIPCHK(c, hipEventElapsedTime(&ms, t.ev[p - 1], t.ev[p]));
         ((p & 1) ? t.overlap_ms : t.serial_ms) += ms;
+        t.phase_ms[p - 1] = ms;
     }
     t.chosen = t.overlap_ms < t.serial_ms ? DASGD_SCHED_OVERLAP : DASGD_SCHED_SERIAL;
     for (int i = 0; i < t.n_ev; ++i) { (void)hipEventDestroy(t.ev[i]); t.ev[i] = nullptr; }
@@ -659,6 +662,13 @@ int dasgd_set_schedule(dasgd_ctx *c, int schedule)
     return DASGD_OK;
 }
 
+int dasgd_set_side_stream_head_start(dasgd_ctx *c, unsigned microseconds)
+{
+    if (!c || microseconds > 200) return DASGD_EINVAL;
+    c->head_start_us = microseconds;
+    return DASGD_OK;
+}
+
 int dasgd_set_side_stream_threshold(dasgd_ctx *c, size_t bytes)
 {
     if (!c) return DASGD_EINVAL;
@@ -813,6 +823,10 @@ static int launch_average(dasgd_ctx *c, int slot, bool *on_side)
         HIPCHK(c, hipEventRecord(c->snap_done[slot], c->main_s));
         HIPCHK(c, hipStreamWaitEvent(c->side_s, c->snap_done[slot], 0));
         s = c->side_s;
+        if (c->head_start_us) {
+            hipLaunchKernelGGL(k_head_start, dim3(1), dim3(kWave), 0, s, c->head_start_us * 100u);
+            HIPCHK(c, hipGetLastError());
+        }
     }
     int rec;
     int rc = prof_open(c, c->zc && c->zc_recon ? DASGD_K_MEAN_RECONSTRUCT : DASGD_K_MEAN, s, &rec);
@@ -1327,6 +1341,13 @@ int dasgd_schedule_in_use(const dasgd_ctx *c, int *schedule, int *settled, doubl
     if (settled) *settled = (!is_auto || c->sched_tuner.chosen >= 0) ? 1 : 0;
     if (overlap_ms) *overlap_ms = c->sched_tuner.overlap_ms;
     if (serial_ms) *serial_ms = c->sched_tuner.serial_ms;
+    return DASGD_OK;
+}
+
+int dasgd_schedule_trial(const dasgd_ctx *c, float *phase_ms)
+{
+    if (!c || !phase_ms) return DASGD_EINVAL;
+    for (int p = 0; p < ScheduleTuner::kPhases - 1; ++p) phase_ms[p] = c->sched_tuner.phase_ms[p];
     return DASGD_OK;
 }
 

@@ -604,4 +604,21 @@ __global__ void __launch_bounds__(kThreads) k_fill_zero(v4f *__restrict__ p, int
         p[i] = z;
 }
 
+// One wavefront that lets about `ticks` ticks of the constant 100 MHz clock pass and exits: launched on
+// the side stream in front of a mean, it gives the kernel that the caller enqueued on the main stream
+// behind the local step a head start.  Which of two kernels that become ready at the same moment is
+// dispatched first decides how they share the chip: a kernel already in place keeps its wave slots and the
+// mean fills the rest, but a mean dispatched first takes every slot it can use and the other kernel only
+// starts as the mean drains (measured on MI355X: a 0.75 ms kernel took 0.96-1.08 ms behind a 0.16 ms mean
+// that won the race by 0.3 us, and 0.75 ms when it was 6 us ahead).  The loop is bounded whatever the
+// clock reads.
+__global__ void __launch_bounds__(kWave) k_head_start(unsigned ticks)
+{
+    const uint64_t t0 = wall_clock64();
+    for (int i = 0; i < 512; ++i) {
+        if (wall_clock64() - t0 >= (uint64_t)ticks) break;
+        __builtin_amdgcn_s_sleep(16);               // 16 x 64 clocks, about half a microsecond
+    }
+}
+
 }  // namespace dasgd

@@ -74,6 +74,9 @@ def test_create_validates_arguments():
             o.set_snapshot(m)
     o.set_snapshot(pkg.SNAPSHOT_COPY); o.set_snapshot(pkg.SNAPSHOT_ZERO_COPY); o.set_snapshot(pkg.SNAPSHOT_AUTO)
     o.set_side_stream_threshold(0); o.set_side_stream_threshold(1 << 40)
+    o.set_side_stream_head_start(0); o.set_side_stream_head_start(200)
+    with pytest.raises(pkg.DasgdError):
+        o.set_side_stream_head_start(201)
     for b in (-2, 12):
         with pytest.raises(DasgdError):
             o.set_band(b)

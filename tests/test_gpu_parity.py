@@ -748,6 +748,21 @@ def test_auto_schedule_settles_and_never_changes_results():
     assert torch.equal(outs[pkg.SCHED_AUTO], outs[pkg.SCHED_SERIAL]) and torch.equal(outs[pkg.SCHED_AUTO], outs[pkg.SCHED_OVERLAP])
 
 
+def test_head_start_of_the_side_stream_mean_never_changes_results():
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=2, d=1, W=8, steps=24, params=custom_param_set([2**18, 4096 * 3 + 8, 1000]))
+    outs = []
+    for us in (None, 0, 200):
+        run = GpuRun(cfg, schedule=pkg.SCHED_OVERLAP, side_threshold=0)
+        if us is not None:
+            run.opt.set_side_stream_head_start(us)
+        for _ in range(cfg.steps):
+            run.step()
+        outs.append(torch.from_numpy(run.weights()))
+        run.close()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
 # ------------------------------------------------------------------------------------------------
 # run length: the default snapshot mode spends the zero-copy reconstruction only on the first steps
 def test_snapshot_auto_switches_to_stored_snapshots_after_its_budget():
