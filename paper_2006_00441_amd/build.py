@@ -10,8 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdasgd.so")
 SOURCES = [os.path.join(CSRC, "dasgd.hip")]
-DEPENDS = SOURCES + [os.path.join(CSRC, "kernels.hpp"), os.path.join(ROOT, "include", "dasgd.h"),
-                     os.path.join(ROOT, "include", "dasgd_diag.h")]
+DEPENDS = SOURCES + [os.path.join(CSRC, h) for h in ("kernels.hpp", "context.hpp", "tuning.hpp", "launch.hpp")] + [
+    os.path.join(ROOT, "include", "dasgd.h"), os.path.join(ROOT, "include", "dasgd_diag.h")]
 STUDY = os.path.join(HERE, "shape_study")            # stand-alone launch-shape study (see csrc/shape_study.hip)
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",

@@ -2,625 +2,10 @@
 // include/dasgd_diag.h, the pending-average ring, and the stream/event schedule that lets the W-way
 // mean run behind the following local steps (paper, Section 3 and Fig. 2: a worker hands its weights to
 // the averaging and immediately continues; the result is applied d local steps later).
-#include "../../include/dasgd.h"
-#include "../../include/dasgd_diag.h"
-#include "kernels.hpp"
+#include "context.hpp"
+#include "tuning.hpp"
+#include "launch.hpp"
 
-#include <cmath>
-#include <cstdlib>
-#include <cstring>
-#include <algorithm>
-#include <deque>
-#include <mutex>
-#include <utility>
-#include <new>
-#include <vector>
-
-using namespace dasgd;
-
-namespace {
-
-constexpr int kGTables = 4;         // device copies of the gradient pointer table, used in rotation
-constexpr size_t kAlign = 256;
-constexpr int64_t kRowAlign = 256;  // library-owned rows start on 1 KiB boundaries
-
-inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
-
-struct Pending {
-    int64_t launch_step;
-    int slot;
-    bool on_side;       // its mean kernel was launched on the side stream
-    bool awaited;       // the main stream already waits for it (or it ran there)
-};
-
-struct ProfRec {
-    int kernel;
-    hipEvent_t start, stop;
-};
-
-// Which band length (see the three-dimensional grids in kernels.hpp) is fastest depends on the row
-// length and on what runs around the kernel, so it is measured where it matters: in the caller's own
-// steps.  The first launches of a kernel kind rotate through the candidates, a few of them bracketed by
-// timing events; finished events are collected with non-blocking queries at later launches (the host
-// never waits), and once every candidate has its samples the fastest is kept.  The band length only
-// permutes which workgroup handles which block: results are bit-identical for every choice.
-struct BandTuner {
-    static constexpr int kMaxCand = 5, kSamples = 3;
-    int cand[kMaxCand] = {5, 8, 9, 10, 11};     // log2 of the band length
-    int n_cand = 0;                             // 0: candidates not yet fitted to the row length
-    double sum_ms[kMaxCand] = {};
-    int done[kMaxCand] = {}, issued[kMaxCand] = {};
-    int64_t launches = 0;
-    int chosen = -1;                            // index into cand once decided
-    struct Rec { int cand; hipEvent_t start, stop; };
-    std::deque<Rec> inflight;
-    std::vector<hipEvent_t> spare;
-};
-
-// Whether the side stream pays depends on what the caller runs between two steps: beside work that
-// leaves wave slots free the mean disappears behind it; beside nothing, or beside a kernel that fills
-// every SIMD, the two cross-stream hand-overs only cost time.  DASGD_SCHED_AUTO therefore measures:
-// after a warm-up phase the schedule alternates between OVERLAP and SERIAL in phases of a few steps, an
-// event on the main stream marks every phase boundary (so the caller's own work is inside the
-// measurement), and once all events have completed -- seen by a non-blocking query at a later step --
-// the schedule with the smaller total is kept.
-struct ScheduleTuner {
-    static constexpr int kPhases = 7;           // phase 0 is the warm-up; 1, 3, 5 OVERLAP; 2, 4, 6 SERIAL
-    int phase = 0, steps_in_phase = 0, phase_len = 8;
-    int chosen = -1;                            // DASGD_SCHED_OVERLAP or DASGD_SCHED_SERIAL once decided
-    hipEvent_t ev[kPhases + 1] = {};
-    int n_ev = 0;
-    double overlap_ms = 0, serial_ms = 0;
-    float phase_ms[kPhases - 1] = {};           // measured phases 1..6 in order, once decided
-};
-
-struct Layout {                     // byte offsets into the workspace
-    size_t recs, gp[kGTables], S, A, total;
-    int64_t P_pad, n_pieces;        // P_pad: floats per snapshot row / average
-    std::vector<int64_t> foff;      // start of each tensor inside such a row
-    bool rows = false;              // rows mirror the replicas' own layout (foff = plain prefix sums)
-};
-
-}  // namespace
-
-struct dasgd_ctx {
-    // problem
-    int W = 0, d = 0, tau = 1;
-    int64_t P = 0;
-    float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
-    int schedule = DASGD_SCHED_AUTO;
-    int fusion = DASGD_FUSE_STEP_MERGE;
-    int snapshot = DASGD_SNAPSHOT_AUTO;
-    int slots = 1;
-    size_t side_min_bytes = (size_t)64 << 20;   // means that move less than this run on the main stream
-    unsigned head_start_us = 20;                // a side-stream mean is held back by this much (k_head_start)
-    // binding
-    bool bound = false, dry = false;
-    int n_tensors = 0;
-    std::vector<int64_t> numel;
-    Layout lay;
-    char *ws = nullptr;
-    hipStream_t main_s = nullptr, side_s = nullptr;
-    // rows addressing: every replica's tensors are one contiguous, 16-byte aligned run of P floats
-    bool xv_rows = false, g_rows = false;
-    RowSet xr = {}, vr = {};
-    ConstRowSet gr = {};
-    // gradient pointer tables
-    std::vector<const float *> g_cached;
-    std::vector<std::pair<uintptr_t, size_t>> owned;    // byte ranges of x, v and the workspace, sorted by start
-    int g_cur = -1;
-    void *g_pinned = nullptr;       // kGTables host staging tables (pinned)
-    hipEvent_t g_ev[kGTables] = {};
-    bool g_ev_live[kGTables] = {};
-    // schedule state
-    int64_t n_done = 0;             // completed local steps; k = n_done - 1
-    int64_t n_launched = 0;         // averages launched so far
-    bool begun_for_k = false;       // dasgd_average_begin already issued for the current k
-    bool snap_valid = false;        // the latest local step prepared an average (snapshot stored, or zero-copy)
-    bool y_in_snap = false;         // ... and stored ONLY the snapshot: x is stale until this step's merge
-    bool mean_deferred = false;     // the mean of snap_slot is launched right after this step's merge
-    bool merged_in_step = false;    // the latest local step already applied this step's merge
-    bool mean_in_step = false;      // ... and already computed the average that average_begin will register
-    bool zc = false;                // the latest local step stored no snapshot: the mean reads x itself
-    bool zc_recon = false;          // ... and x already holds the merged weights: undo the merge on the mean
-    int zc_old_slot = 0;            // ... with the average in this slot
-    float zc_xi = 0.25f;            // ... and this xi
-    int snap_slot = 0;
-    int sched_now = DASGD_SCHED_OVERLAP;   // the schedule in effect for the step being issued (fixed per step)
-    int band_fixed = -1;            // >= 0: log2 of the band length set by the caller; -1: measured (BandTuner)
-    BandTuner tuner[DASGD_K_COUNT];
-    ScheduleTuner sched_tuner;
-    std::deque<Pending> pending;
-    std::vector<hipEvent_t> snap_done, avg_done;
-    // profiling
-    int prof_every = 0;             // 0: off; n: time one launch in n of every kernel kind
-    int prof_max = 0;
-    int64_t prof_seen[DASGD_K_COUNT] = {};
-    std::vector<ProfRec> prof_recs;
-    std::vector<ProfRec> prof_pool;
-    int last_hip = 0;
-};
-
-namespace {
-
-#define HIPCHK(ctx, expr)                                   \
-    do {                                                    \
-        hipError_t e_ = (expr);                             \
-        if (e_ != hipSuccess) {                             \
-            (ctx)->last_hip = (int)e_;                      \
-            return DASGD_EHIP;                              \
-        }                                                   \
-    } while (0)
-
-bool shapes_ok(const dasgd_ctx *c, int n_tensors, const int64_t *numel)
-{
-    if (!c || n_tensors < 1 || !numel) return false;
-    int64_t sum = 0;
-    for (int t = 0; t < n_tensors; ++t) {
-        if (numel[t] < 1 || numel[t] >= (1ll << 32)) return false;
-        sum += numel[t];
-    }
-    return sum == c->P;
-}
-
-// Rows of the library-owned buffers (snapshots, averages) either pad every tensor to a 256-byte
-// boundary (so that the record kernels can use 128-bit accesses on them whatever the tensor sizes) or,
-// when every replica is one contiguous run, mirror that run (column c of a snapshot row is column c of
-// the replica).  The byte offsets of the padded layout are used in both cases: the workspace size must
-// not depend on pointers that dasgd_workspace_bytes never sees.
-Layout make_layout(const dasgd_ctx *c, int n_tensors, const int64_t *numel, bool rows = false)
-{
-    Layout L;
-    L.foff.resize(n_tensors);
-    int64_t f = 0, fp = 0, np = 0;
-    for (int t = 0; t < n_tensors; ++t) {
-        L.foff[t] = rows ? fp : f;
-        fp += numel[t];
-        f += (numel[t] + kPad - 1) / kPad * kPad;
-        np += (numel[t] + kPiece - 1) / kPiece;
-    }
-    L.rows = rows;
-    f = (f + kRowAlign - 1) / kRowAlign * kRowAlign + kRowAlign;
-    L.P_pad = f;                    // sizes below always use the padded row length
-    L.n_pieces = np;
-    const size_t tbl = sizeof(void *) * (size_t)c->W * (size_t)n_tensors;
-    size_t o = 0;
-    L.recs = o;   o += align_up(sizeof(Rec) * (size_t)c->W * (size_t)np);
-    for (int b = 0; b < kGTables; ++b) { L.gp[b] = o; o += align_up(tbl); }
-    L.S = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)c->W * (size_t)L.P_pad);
-    L.A = o;      o += align_up(sizeof(float) * (size_t)c->slots * (size_t)L.P_pad);
-    L.total = o;
-    if (rows) L.P_pad = (c->P + kRowAlign - 1) / kRowAlign * kRowAlign;
-    return L;
-}
-
-// True when, for every replica j, ptr[j*n + t] == ptr[j*n] + (unpadded offset of t) and ptr[j*n] is
-// 16-byte aligned, with P a multiple of 4 below 2^33 and at most kMaxRows replicas: every replica is one
-// contiguous run of P floats (rows of a matrix with any stride, or one arena per replica).
-template <typename T>
-bool is_rows(const dasgd_ctx *c, int n_tensors, const int64_t *numel, T *const *ptr)
-{
-    if (c->W > kMaxRows || c->P % 4 != 0 || c->P / 4 > (1ll << 31) - 256) return false;
-    for (int j = 0; j < c->W; ++j) {
-        T *base = ptr[(size_t)j * n_tensors];
-        if (reinterpret_cast<uintptr_t>(base) & 15u) return false;
-        int64_t off = 0;
-        for (int t = 0; t < n_tensors; ++t) {
-            if (ptr[(size_t)j * n_tensors + t] != base + off) return false;
-            off += numel[t];
-        }
-    }
-    return true;
-}
-
-// False only when the runtime knows the allocation that holds p and [p, p + bytes) leaves it.  (Memory
-// the runtime cannot place -- not allocated through it -- cannot be checked and passes.)  A kernel that
-// runs past a buffer faults the GPU; a size mistake of the caller's is better met with an error code.
-// `last` remembers the allocation found for the previous pointer of the same pass: tensors usually
-// sit side by side in one allocation, and asking the runtime costs about half a microsecond each time.
-struct DeviceRange {
-    uintptr_t base = 0;
-    size_t size = 0;
-};
-bool range_ok(const void *p, size_t bytes, DeviceRange *last = nullptr)
-{
-    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
-    DeviceRange r;
-    if (last && last->size && a >= last->base && a - last->base < last->size) {
-        r = *last;
-    } else {
-        hipDeviceptr_t base = nullptr;
-        size_t size = 0;
-        if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
-            (void)hipGetLastError();
-            return true;
-        }
-        r.base = reinterpret_cast<uintptr_t>(base);
-        r.size = size;
-        if (last) *last = r;
-    }
-    return a >= r.base && bytes <= r.size && a - r.base <= r.size - bytes;
-}
-
-// True if any two of the byte ranges [first, first + second) overlap (sorts its argument).
-bool any_overlap(std::vector<std::pair<uintptr_t, size_t>> &iv)
-{
-    std::sort(iv.begin(), iv.end());
-    for (size_t i = 1; i < iv.size(); ++i)
-        if (iv[i].first < iv[i - 1].first + iv[i - 1].second) return true;
-    return false;
-}
-
-inline float *snap_ptr(const dasgd_ctx *c, int slot)
-{
-    return reinterpret_cast<float *>(c->ws + c->lay.S) + (size_t)slot * (size_t)c->W * (size_t)c->lay.P_pad;
-}
-inline float *avg_ptr(const dasgd_ctx *c, int slot)
-{
-    return reinterpret_cast<float *>(c->ws + c->lay.A) + (size_t)slot * (size_t)c->lay.P_pad;
-}
-
-// The schedule in effect for the step being issued.
-inline int effective_schedule(const dasgd_ctx *c)
-{
-    if (c->schedule != DASGD_SCHED_AUTO) return c->schedule;
-    const ScheduleTuner &t = c->sched_tuner;
-    if (t.chosen >= 0) return t.chosen;
-    if (t.phase >= ScheduleTuner::kPhases) return DASGD_SCHED_OVERLAP;       // measured, result still to come
-    return (t.phase == 0 || (t.phase & 1)) ? DASGD_SCHED_OVERLAP : DASGD_SCHED_SERIAL;
-}
-
-// The mean goes to the side stream in the overlap schedules -- unless it is so small that the two
-// cross-stream hand-overs (main -> side before it, side -> main after it; 6-10 us each on MI355X)
-// cost more than running it in line could ever lose.
-inline bool side_stream_mean(const dasgd_ctx *c)
-{
-    const int s = c->sched_now;
-    if (s != DASGD_SCHED_OVERLAP && s != DASGD_SCHED_OVERLAP_FREE) return false;
-    const size_t mean_bytes = sizeof(float) * (size_t)(c->W + 1) * (size_t)c->lay.P_pad;
-    return mean_bytes >= c->side_min_bytes;
-}
-
-inline bool begin_due(const dasgd_ctx *c)
-{
-    return c->n_done > 0 && (c->n_done % c->tau) == 0 && !c->begun_for_k;     // (k+1) mod tau == 0
-}
-inline bool merge_due(const dasgd_ctx *c)
-{
-    return !c->pending.empty() && c->pending.front().launch_step == (c->n_done - 1) - c->d;
-}
-
-// Steps for which DASGD_SNAPSHOT_AUTO takes the zero-copy path.  Measured against a double-precision run
-// (W = 8, tau = 1, d = 2, random gradients) the deviation of every fp32 implementation grows like the
-// square root of the step count K: about 1.3e-7 sqrt(K) of the weight scale with stored snapshots, and
-// 2.2e-7 sqrt(K) with the reconstruction at xi = 0.25, whose extra term scales with 1/xi.  The budget keeps
-// the reconstruction's share small enough that the whole run stays below 1e-5 for 3000 steps with a
-// quarter to spare (sqrt(500 * 2.2e-7^2 + 2500 * 1.3e-7^2) = 7.2e-6): 500 steps at xi >= 0.25, fewer in
-// proportion to xi^2 below, none below xi = 1/8.
-inline int64_t zero_copy_budget(float xi)
-{
-    if (xi < 0.125f) return 0;
-    const double r = std::min(1.0, (double)xi / 0.25);
-    return (int64_t)(500.0 * r * r);
-}
-
-// Timing brackets for one launch (no-ops unless profiling).
-int prof_open(dasgd_ctx *c, int kernel, hipStream_t s, int *rec_index)
-{
-    *rec_index = -1;
-    if (c->prof_every <= 0) return DASGD_OK;
-    if ((c->prof_seen[kernel]++ % c->prof_every) != 0 || (int)c->prof_recs.size() >= c->prof_max) return DASGD_OK;
-    ProfRec r;
-    if (!c->prof_pool.empty()) {
-        r = c->prof_pool.back();
-        c->prof_pool.pop_back();
-    } else {
-        HIPCHK(c, hipEventCreate(&r.start));
-        HIPCHK(c, hipEventCreate(&r.stop));
-    }
-    r.kernel = kernel;
-    HIPCHK(c, hipEventRecord(r.start, s));
-    c->prof_recs.push_back(r);
-    *rec_index = (int)c->prof_recs.size() - 1;
-    return DASGD_OK;
-}
-int prof_close(dasgd_ctx *c, hipStream_t s, int rec_index)
-{
-    if (rec_index < 0) return DASGD_OK;
-    HIPCHK(c, hipEventRecord(c->prof_recs[rec_index].stop, s));
-    return DASGD_OK;
-}
-
-// Collect the trials that have finished (never waits).
-int band_poll(dasgd_ctx *c, BandTuner &t)
-{
-    while (!t.inflight.empty()) {
-        BandTuner::Rec &r = t.inflight.front();
-        const hipError_t q = hipEventQuery(r.stop);
-        if (q == hipErrorNotReady) {
-            (void)hipGetLastError();            // "not ready" is an answer, not a failure: do not leave it behind
-            break;
-        }
-        HIPCHK(c, q);
-        float ms = 0.f;
-        HIPCHK(c, hipEventElapsedTime(&ms, r.start, r.stop));
-        t.sum_ms[r.cand] += ms;
-        t.done[r.cand] += 1;
-        t.spare.push_back(r.start);
-        t.spare.push_back(r.stop);
-        t.inflight.pop_front();
-    }
-    return DASGD_OK;
-}
-
-// Collect, and keep the fastest candidate once every one has its samples.
-int band_decide(dasgd_ctx *c, BandTuner &t)
-{
-    const int rc = band_poll(c, t);
-    if (rc != DASGD_OK) return rc;
-    for (int i = 0; i < t.n_cand; ++i)
-        if (t.done[i] < BandTuner::kSamples) return DASGD_OK;
-    int best = 0;
-    for (int i = 1; i < t.n_cand; ++i)
-        if (t.sum_ms[i] / t.done[i] < t.sum_ms[best] / t.done[best]) best = i;
-    t.chosen = best;
-    for (hipEvent_t e : t.spare) (void)hipEventDestroy(e);
-    t.spare.clear();
-    return DASGD_OK;
-}
-
-// Grid (gx, W, gz) that covers `blocks` workgroups per replica in bands of 2^log_band blocks per L2
-// partition.  The band is lengthened until gz fits the 16-bit limit of a grid's z dimension and
-// shortened to what the row needs.
-struct BandGrid { dim3 grid; int log_band; };
-BandGrid band_grid(uint64_t blocks, int W, int log_band)
-{
-    if (blocks < 1) blocks = 1;
-    int lb = log_band < 0 ? 0 : log_band;
-    while (lb > 0 && (8ull << (lb - 1)) >= blocks) --lb;               // one band already holds the row
-    while ((blocks + (8ull << lb) - 1) / (8ull << lb) > 65535ull) ++lb;
-    const uint64_t gx = 8ull << lb, gz = (blocks + gx - 1) / gx;
-    BandGrid g;
-    g.grid = dim3((unsigned)gx, (unsigned)W, (unsigned)gz);
-    g.log_band = lb;
-    return g;
-}
-
-// Choice for the next launch of the kernel that tuner t serves, over `blocks` workgroups per replica:
-// the log2 of a band length.  *trial >= 0: the launch is a timed trial, band_close must follow it.
-int band_pick(dasgd_ctx *c, BandTuner &t, uint64_t blocks, int *log_band, int *trial)
-{
-    *trial = -1;
-    if (c->band_fixed >= 0) {
-        *log_band = band_grid(blocks, 1, c->band_fixed).log_band;
-        return DASGD_OK;
-    }
-    if (t.n_cand == 0) {                        // fit the candidates to the row length, drop duplicates
-        int n = 0;
-        for (int i = 0; i < BandTuner::kMaxCand; ++i) {
-            const int lb = band_grid(blocks, 1, t.cand[i]).log_band;
-            bool dup = false;
-            for (int k = 0; k < n; ++k) dup = dup || t.cand[k] == lb;
-            if (!dup) t.cand[n++] = lb;
-        }
-        t.n_cand = n;
-        if (n == 1) t.chosen = 0;
-    }
-    if (t.chosen < 0) {
-        const int rc = band_decide(c, t);
-        if (rc != DASGD_OK) return rc;
-    }
-    if (t.chosen >= 0) {
-        *log_band = t.cand[t.chosen];
-        return DASGD_OK;
-    }
-    const int64_t n = t.launches++;
-    int pick = -1;
-    if (n > 0)                                  // (the first launch of a kind runs cold: not timed)
-        for (int i = 0; i < t.n_cand; ++i)
-            if (t.issued[i] < BandTuner::kSamples && (pick < 0 || t.issued[i] < t.issued[pick])) pick = i;
-    if (pick < 0) {                             // cold launch, or all trials issued and results still to come
-        *log_band = t.cand[t.n_cand / 2];
-        return DASGD_OK;
-    }
-    BandTuner::Rec r;
-    r.cand = pick;
-    for (hipEvent_t *e : {&r.start, &r.stop}) {
-        if (!t.spare.empty()) { *e = t.spare.back(); t.spare.pop_back(); }
-        else HIPCHK(c, hipEventCreate(e));
-    }
-    HIPCHK(c, hipEventRecord(r.start, c->main_s));
-    t.inflight.push_back(r);
-    t.issued[pick] += 1;
-    *log_band = t.cand[pick];
-    *trial = pick;
-    return DASGD_OK;
-}
-int band_close(dasgd_ctx *c, BandTuner &t, int trial)
-{
-    if (trial < 0) return DASGD_OK;
-    HIPCHK(c, hipEventRecord(t.inflight.back().stop, c->main_s));
-    return DASGD_OK;
-}
-
-// DASGD_SCHED_AUTO: one call per local step.  Advances the phases, decides once the marks have completed, and
-// returns in *mark the event (or null) that this step must record on the main stream -- AFTER it has made the
-// main stream wait for the means still running on the side stream, so that a mean is charged to the phase
-// that launched it and not to the next one.
-int schedule_tick(dasgd_ctx *c, hipEvent_t *mark)
-{
-    *mark = nullptr;
-    ScheduleTuner &t = c->sched_tuner;
-    if (c->schedule != DASGD_SCHED_AUTO || t.chosen >= 0) return DASGD_OK;
-    if (t.phase < ScheduleTuner::kPhases) {
-        if (t.steps_in_phase == 0 && t.phase >= 1) {            // boundary: start of a measured phase
-            const int i = t.phase - 1;
-            if (!t.ev[i]) { HIPCHK(c, hipEventCreate(&t.ev[i])); t.n_ev = i + 1; }
-            *mark = t.ev[i];
-        }
-        ++t.steps_in_phase;
-        bool over = t.steps_in_phase >= t.phase_len;
-        if (t.phase == 0) {
-            // the warm-up lasts two phases and as long as band lengths are still being tried (their timing
-            // events and slower candidates would fall into some phases and not others), within reason
-            bool bands_busy = false;
-            for (const BandTuner &b : c->tuner) bands_busy = bands_busy || (b.n_cand > 0 && b.chosen < 0);
-            over = t.steps_in_phase >= 2 * t.phase_len && t.steps_in_phase % t.phase_len == 0 &&
-                   (!bands_busy || t.steps_in_phase >= 32 * t.phase_len);
-        }
-        if (over) {
-            t.steps_in_phase = 0;
-            t.phase += 1;
-        }
-        return DASGD_OK;
-    }
-    const int last = ScheduleTuner::kPhases - 1;                // the mark that ends the last measured phase
-    if (!t.ev[last]) {
-        HIPCHK(c, hipEventCreate(&t.ev[last]));
-        t.n_ev = last + 1;
-        *mark = t.ev[last];
-        return DASGD_OK;
-    }
-    const hipError_t q = hipEventQuery(t.ev[last]);
-    if (q == hipErrorNotReady) {
-        (void)hipGetLastError();
-        return DASGD_OK;
-    }
-    HIPCHK(c, q);
-    t.overlap_ms = t.serial_ms = 0;
-    for (int p = 1; p < ScheduleTuner::kPhases; ++p) {          // phase p lies between marks p-1 and p
-        float ms = 0.f;
-        HIPCHK(c, hipEventElapsedTime(&ms, t.ev[p - 1], t.ev[p]));
-        ((p & 1) ? t.overlap_ms : t.serial_ms) += ms;
-        t.phase_ms[p - 1] = ms;
-    }
-    t.chosen = t.overlap_ms < t.serial_ms ? DASGD_SCHED_OVERLAP : DASGD_SCHED_SERIAL;
-    for (int i = 0; i < t.n_ev; ++i) { (void)hipEventDestroy(t.ev[i]); t.ev[i] = nullptr; }
-    t.n_ev = 0;
-    return DASGD_OK;
-}
-
-// Are the rows 128-byte aligned relative to each other?  (If not, neighbouring column windows of the mean
-// kernels share cache lines, and the kernels issue runs of windows on one L2 partition.)
-bool rows_share_lines(const ConstRowSet &r, int W)
-{
-    for (int j = 0; j < W; ++j)
-        if ((reinterpret_cast<uintptr_t>(r.p[j]) - reinterpret_cast<uintptr_t>(r.p[0])) & 127u) return true;
-    return (reinterpret_cast<uintptr_t>(r.p[0]) & 127u) != 0;
-}
-
-inline unsigned mean_grid(unsigned row4) { return ((row4 + kWave - 1) / kWave + 63u) / 64u * 64u; }
-
-// W-way mean of `row_elems` floats per row (a multiple of 4, rows 16-byte aligned) into A.
-// rows: the W row pointers (W <= kMaxRows); or strided != nullptr: rows at strided + j * stride floats.
-hipError_t launch_mean_of(int W, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
-{
-    const unsigned row4 = (unsigned)(row_elems / 4);
-    v4f *A4 = reinterpret_cast<v4f *>(A);
-    const float inv_w = 1.0f / (float)W;
-    ConstRowSet r = {};
-    if (rows) r = *rows;
-    else if (W <= kMaxRows)
-        for (int j = 0; j < W; ++j) r.p[j] = strided + (int64_t)j * stride;
-    if (W > kMaxRows) {
-        hipLaunchKernelGGL(k_mean_strided, dim3((row4 + kWave - 1) / kWave), dim3(kWave), 0, s,
-                           reinterpret_cast<const v4f *>(strided), stride / 4, A4, row4, W, inv_w);
-        return hipGetLastError();
-    }
-    const bool runs = rows_share_lines(r, W);
-    const dim3 grid(mean_grid(row4));
-#define DASGD_LAUNCH_MEAN(WT, NW)                                                                               \
-    do {                                                                                                        \
-        if (runs) hipLaunchKernelGGL((k_mean_rows<WT, NW, true>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w);  \
-        else      hipLaunchKernelGGL((k_mean_rows<WT, NW, false>), grid, dim3(kWave * NW), 0, s, r, A4, row4, inv_w); \
-    } while (0)
-    switch (W) {                // rows split over wavefronts + LDS where that measured faster
-    case 4:  DASGD_LAUNCH_MEAN(4, 4);  break;
-    case 8:  DASGD_LAUNCH_MEAN(8, 4);  break;
-    case 16: DASGD_LAUNCH_MEAN(16, 8); break;
-    default:
-        if (runs) hipLaunchKernelGGL((k_mean_any<true>), grid, dim3(kWave), 0, s, r, A4, row4, W, inv_w);
-        else      hipLaunchKernelGGL((k_mean_any<false>), grid, dim3(kWave), 0, s, r, A4, row4, W, inv_w);
-        break;
-    }
-#undef DASGD_LAUNCH_MEAN
-    return hipGetLastError();
-}
-int launch_mean(dasgd_ctx *c, hipStream_t s, const ConstRowSet *rows, const float *strided, int64_t stride, float *A, int64_t row_elems)
-{
-    HIPCHK(c, launch_mean_of(c->W, s, rows, strided, stride, A, row_elems));
-    return DASGD_OK;
-}
-
-thread_local int g_last_hip = 0;        // HIP error of the latest failed call that has no context
-
-// Scratch memory of dasgd_average_now_static: the average of one call.  Every GPU the library runs on holds
-// its own copy of the array, at its own address, until the process ends.  Host code must not use the name
-// as an address: the per-device address comes from hipGetSymbolAddress, once per device.
-constexpr int64_t kStaticScratchFloats = 32ll << 20;        // 128 MiB
-static __device__ __align__(256) float scratch[kStaticScratchFloats];
-constexpr int kMaxDevices = 64;
-float *g_scratch_ptr[kMaxDevices] = {};
-std::mutex g_scratch_mutex;
-
-// Address of the current device's copy of `scratch` (looked up on the first call on that device).
-int static_scratch(float **out)
-{
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) return DASGD_EINVAL;
-    if (e == hipSuccess) {
-        std::lock_guard<std::mutex> lock(g_scratch_mutex);
-        if (!g_scratch_ptr[dev]) {
-            void *p = nullptr;
-            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
-            if (e == hipSuccess) g_scratch_ptr[dev] = static_cast<float *>(p);
-        }
-        *out = g_scratch_ptr[dev];
-    }
-    if (e != hipSuccess) {
-        g_last_hip = (int)e;
-        return DASGD_EHIP;
-    }
-    return DASGD_OK;
-}
-
-// The blocking average of dasgd_average_now: A <- mean of the rows, rows <- xi row + (1 - xi) A.  Launches
-// two kernels on `s` and allocates nothing.
-int average_now(int W, int64_t P, float *const *x_rows, float xi, float *A, hipStream_t s)
-{
-    if (W < 1 || W > kMaxRows || P < 4 || P % 4 != 0 || P / 4 > (1ll << 31) - 256) return DASGD_EINVAL;
-    if (!x_rows || !A || !(xi >= 0.f && xi <= 1.f)) return DASGD_EINVAL;
-    std::pair<uintptr_t, size_t> iv[kMaxRows + 1];
-    RowSet xr = {};
-    ConstRowSet cr = {};
-    for (int j = 0; j < W; ++j) {
-        if (!x_rows[j] || (reinterpret_cast<uintptr_t>(x_rows[j]) & 15u)) return DASGD_EINVAL;
-        if (!range_ok(x_rows[j], sizeof(float) * (size_t)P)) return DASGD_EINVAL;
-        xr.p[j] = x_rows[j];
-        cr.p[j] = x_rows[j];
-        iv[j] = {reinterpret_cast<uintptr_t>(x_rows[j]), sizeof(float) * (size_t)P};
-    }
-    iv[W] = {reinterpret_cast<uintptr_t>(A), sizeof(float) * (size_t)P};
-    std::sort(iv, iv + W + 1);
-    for (int i = 1; i <= W; ++i)
-        if (iv[i].first < iv[i - 1].first + iv[i - 1].second) return DASGD_EINVAL;     // rows and scratch must not share bytes
-    hipError_t e = launch_mean_of(W, s, &cr, nullptr, 0, A, P);
-    if (e == hipSuccess) {
-        const unsigned row4 = (unsigned)(P / 4);
-        const dim3 grid = band_grid(rows_blocks(row4), W, 9).grid;
-        hipLaunchKernelGGL((k_merge_rows<false>), grid, dim3(kWave), 0, s, xr, static_cast<const v4f *>(nullptr), (int64_t)0,
-                           reinterpret_cast<const v4f *>(A), row4, 1.0f - xi);
-        e = hipGetLastError();
-    }
-    if (e != hipSuccess) {
-        g_last_hip = (int)e;
-        return DASGD_EHIP;
-    }
-    return DASGD_OK;
-}
-
-}  // namespace
 
 // ------------------------------------------------------------------------------------------------
 extern "C" {
