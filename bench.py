@@ -775,6 +775,14 @@ def main() -> int:
                     mm.pop("_run").close()
                     a.close()
                     layouts[name][lay] = brief(mm, name, lay)
+        # the xi / d / tau study on the quadratic, compact (all columns: bench.py --sweep)
+        sw = sweep_quadratic()
+        out["parameter_study"] = {
+            "what": sw["sweep"] + f"; decay rate per step between steps {sw['K0']} and {sw['K1']}: [axis, xi, tau, d, measured on the GPU, "
+                    "predicted by the linear recurrence, spectral radius of one period]",
+            "rows": [[r["axis"], r["xi"], r["tau"], r["d"], r["measured_rate_per_step"], r["recurrence_rate_per_step"],
+                      r["spectral_radius_per_step"]] for r in sw["rows"]],
+            "max_abs_rate_difference": max(abs(r["measured_rate_per_step"] - r["recurrence_rate_per_step"]) for r in sw["rows"])}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     out["bench_seconds"] = round(time.perf_counter() - t_start, 1)
