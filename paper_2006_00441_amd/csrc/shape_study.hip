@@ -972,6 +972,15 @@ int main(int argc, char **argv)
             case 8:  hipLaunchKernelGGL((mean_rows<8, 4>), dim3(bpr), dim3(256), 0, 0, rows, A2, row4, 1.0f / W); break;
             default: hipLaunchKernelGGL((mean_rows<16, 8>), dim3(bpr), dim3(512), 0, 0, rows, A2, row4, 1.0f / W); break;
             } });
+        // how many wavefronts share the W rows of a window
+#define MEAN_SPLIT(WT, NW) run("rows, " #NW " wavefronts per workgroup (" #WT "/" #NW " rows each)", B_MEAN, [&] { \
+            hipLaunchKernelGGL((mean_rows<WT, NW>), dim3(bpr), dim3(64 * NW), 0, 0, rows, A2, row4, 1.0f / W); })
+        switch (W) {
+        case 4:  MEAN_SPLIT(4, 1); MEAN_SPLIT(4, 2); MEAN_SPLIT(4, 4); break;
+        case 8:  MEAN_SPLIT(8, 1); MEAN_SPLIT(8, 2); MEAN_SPLIT(8, 4); MEAN_SPLIT(8, 8); break;
+        default: MEAN_SPLIT(16, 1); MEAN_SPLIT(16, 2); MEAN_SPLIT(16, 4); MEAN_SPLIT(16, 8); MEAN_SPLIT(16, 16); break;
+        }
+#undef MEAN_SPLIT
     }
     return 0;
 }
