@@ -155,6 +155,8 @@ class Arena:
         torch = self.torch
         if not kind or kind == "none":
             return lambda: None
+        if callable(kind):
+            return kind
         if kind == "gemm":
             if self._gemm is None:
                 with torch.cuda.stream(self.main):
@@ -382,6 +384,101 @@ def best_of(run: Run, steps: int, warmup: int, reps: int = 3) -> float:
     for _ in range(warmup):
         run.step()
     return min(run.timed(steps)[0] for _ in range(reps)) / steps * 1e3
+
+
+class LtGemm:
+    """The overlap workload's GEMM issued through hipBLASLt with a chosen algorithm (bench_gemm.hip): every
+    algorithm the library has for the problem, timed alone, so that the one that makes the whole step
+    fastest can be taken instead of the one its heuristic ranks first for the GEMM alone."""
+    WORKSPACE = 256 << 20
+
+    def __init__(self, arena: "Arena"):
+        torch = arena.torch
+        L = ctypes.CDLL(os.path.join(ROOT, "bench_gemm.so"))
+        L.bench_gemm_open.argtypes = [ctypes.c_int, ctypes.c_size_t]
+        L.bench_gemm_workspace.restype = ctypes.c_size_t
+        L.bench_gemm_run.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_size_t, ctypes.c_void_p]
+        L.bench_gemm_name.argtypes = [ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+        self.L, self.arena = L, arena
+        self.n = L.bench_gemm_open(8192, self.WORKSPACE)
+        if self.n <= 0:
+            raise RuntimeError(f"bench_gemm_open: {self.n}")
+        self.first = L.bench_gemm_first_by_heuristic()
+        arena.stand_in("gemm")                       # builds the seeded operands
+        self.a, self.b, self.c = arena._gemm
+        self.ws = torch.empty(self.WORKSPACE, dtype=torch.uint8, device=arena.dev)
+        self.alone_ms = {}
+
+    def name(self, i: int) -> str:
+        buf = ctypes.create_string_buffer(1024)
+        self.L.bench_gemm_name(i, buf, 1024)
+        return buf.value.decode()
+
+    def tile(self, i: int) -> str:
+        import re
+        m = re.search(r"MT\d+x\d+x\d+_MI\d+x\d+x\d+", self.name(i))
+        return m.group(0) if m else "?"
+
+    def run(self, i: int) -> None:
+        rc = self.L.bench_gemm_run(i, self.a.data_ptr(), self.b.data_ptr(), self.c.data_ptr(), self.ws.data_ptr(),
+                                   self.WORKSPACE, self.arena.main.cuda_stream)
+        if rc:
+            raise RuntimeError(f"bench_gemm_run({i}): {rc}")
+
+    def time_all(self) -> None:
+        """Milliseconds of every algorithm alone (mean of three after one untimed run; an algorithm whose
+        first run takes more than 5 ms is dropped)."""
+        torch, main = self.arena.torch, self.arena.main
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        for i in range(self.n):
+            e0.record(main); self.run(i); e1.record(main); torch.cuda.synchronize()
+            if e0.elapsed_time(e1) > 5.0:
+                continue
+            e0.record(main)
+            for _ in range(3):
+                self.run(i)
+            e1.record(main); torch.cuda.synchronize()
+            self.alone_ms[i] = e0.elapsed_time(e1) / 3
+
+    def close(self) -> None:
+        self.L.bench_gemm_close()
+        self.ws = self.a = self.b = self.c = None
+
+
+def best_algorithm_study(arena: Arena, steps: int, warmup: int):
+    """The overlap-stress step with the GEMM algorithm chosen for the whole step: among hipBLASLt's algorithms
+    within 20 % of the fastest alone, the one with the shortest step under the OVERLAP schedule; then the
+    usual three schedules with it, beside the serial step with the algorithm the heuristic ranks first."""
+    pkg = arena.pkg
+    lt = LtGemm(arena)
+    try:
+        lt.time_all()
+        order = sorted(lt.alone_ms, key=lt.alone_ms.get)
+        fastest = order[0]
+        cands = [i for i in order if lt.alone_ms[i] <= 1.2 * lt.alone_ms[fastest]][:8]
+        quick = {}
+        for i in cands:
+            r = arena.context(schedule=pkg.SCHED_OVERLAP, stand_in=lambda i=i: lt.run(i))
+            quick[i] = best_of(r, 24, 8, reps=2)
+            r.close()
+        chosen = min(quick, key=quick.get)
+        out = overlap_study(arena, steps, warmup, lambda: lt.run(chosen),
+                            f"bf16 GEMM 8192^3, hipBLASLt algorithm {lt.tile(chosen)} (library index "
+                            f"{lt.L.bench_gemm_library_index(chosen)}), chosen for the whole step")
+        ref = lt.first if lt.first in lt.alone_ms else fastest
+        r = arena.context(schedule=pkg.SCHED_SERIAL, stand_in=lambda: lt.run(ref))
+        s0_ref = best_of(r, steps, warmup)
+        r.close()
+        out["algorithms_supported"] = lt.n
+        out["gemm_alone_ms"] = {"chosen": round(lt.alone_ms[chosen], 4), "heuristic_first": round(lt.alone_ms[ref], 4),
+                                "heuristic_first_tile": lt.tile(ref)}
+        out["candidates_S1_ms"] = {lt.tile(i): round(t, 4) for i, t in quick.items()}
+        out["ms_per_step"]["S0_serial_with_the_heuristics_first_algorithm"] = round(s0_ref, 4)
+        out["speedup_over_serial_with_the_heuristics_first_algorithm"] = round(s0_ref / out["ms_per_step"]["S1_overlap"], 4)
+        return out
+    finally:
+        lt.close()
 
 
 def overlap_study(arena: Arena, steps: int, warmup: int, stand_in, label: str):
@@ -752,6 +849,11 @@ def main() -> int:
                 if have_standin:
                     ov["with_register_light_stand_in"] = overlap_study(a, 50, 10, "alu", "ALU-bound kernel, 4 waves/SIMD, 16 VGPRs "
                                                                        "(NOT the benchmark's stand-in: what the schedule hides when a second kernel can share a SIMD)")
+                if os.path.exists(os.path.join(ROOT, "bench_gemm.so")):
+                    try:
+                        ov["with_compute_stand_in_algorithm_chosen_for_the_step"] = best_algorithm_study(a, 50, 10)
+                    except Exception as e:      # context, like the partitioned streams below
+                        ov["with_compute_stand_in_algorithm_chosen_for_the_step"] = {"error": str(e)}
                 out["overlap"] = ov
                 out["algorithms"] = compare_algorithms(a, 40, 8)
             a.close()
