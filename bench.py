@@ -395,13 +395,13 @@ class LtGemm:
     def __init__(self, arena: "Arena"):
         torch = arena.torch
         L = ctypes.CDLL(os.path.join(ROOT, "bench_gemm.so"))
-        L.bench_gemm_open.argtypes = [ctypes.c_int, ctypes.c_size_t]
+        L.bench_gemm_open.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int]
         L.bench_gemm_workspace.restype = ctypes.c_size_t
         L.bench_gemm_run.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]
         L.bench_gemm_name.argtypes = [ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
         self.L, self.arena = L, arena
-        self.n = L.bench_gemm_open(8192, self.WORKSPACE)
+        self.n = L.bench_gemm_open(8192, self.WORKSPACE, 0, 0)      # as torch.matmul(a, b) issues it
         if self.n <= 0:
             raise RuntimeError(f"bench_gemm_open: {self.n}")
         self.first = L.bench_gemm_first_by_heuristic()

@@ -39,10 +39,11 @@ void close_all()
 
 extern "C" {
 
-// Prepare C = A * B for n x n bf16 matrices (column-major, no transposes, fp32 accumulation, bf16 result)
-// and collect every algorithm of the library that supports the problem with at most max_workspace bytes
-// of workspace.  Returns the number of algorithms (>= 1) or a negative hipBLAS status.
-int bench_gemm_open(int n, size_t max_workspace)
+// Prepare C = op(A) * op(B) for n x n bf16 matrices (column-major, op = transpose if trans_a / trans_b is
+// non-zero, fp32 accumulation, bf16 result) and collect every algorithm of the library that supports the
+// problem with at most max_workspace bytes of workspace.  Returns the number of algorithms (>= 1) or a
+// negative hipBLAS status.
+int bench_gemm_open(int n, size_t max_workspace, int trans_a, int trans_b)
 {
     close_all();
     if (n < 256 || n % 256) return -1;
@@ -57,15 +58,15 @@ int bench_gemm_open(int n, size_t max_workspace)
     } while (0)
     BLT(hipblasLtCreate(&G.handle));
     BLT(hipblasLtMatmulDescCreate(&G.desc, HIPBLAS_COMPUTE_32F, HIP_R_32F));
-    const hipblasOperation_t op = HIPBLAS_OP_N;
-    BLT(hipblasLtMatmulDescSetAttribute(G.desc, HIPBLASLT_MATMUL_DESC_TRANSA, &op, sizeof(op)));
-    BLT(hipblasLtMatmulDescSetAttribute(G.desc, HIPBLASLT_MATMUL_DESC_TRANSB, &op, sizeof(op)));
+    const hipblasOperation_t op_a = trans_a ? HIPBLAS_OP_T : HIPBLAS_OP_N, op_b = trans_b ? HIPBLAS_OP_T : HIPBLAS_OP_N;
+    BLT(hipblasLtMatmulDescSetAttribute(G.desc, HIPBLASLT_MATMUL_DESC_TRANSA, &op_a, sizeof(op_a)));
+    BLT(hipblasLtMatmulDescSetAttribute(G.desc, HIPBLASLT_MATMUL_DESC_TRANSB, &op_b, sizeof(op_b)));
     BLT(hipblasLtMatrixLayoutCreate(&G.a, HIP_R_16BF, n, n, n));
     BLT(hipblasLtMatrixLayoutCreate(&G.b, HIP_R_16BF, n, n, n));
     BLT(hipblasLtMatrixLayoutCreate(&G.c, HIP_R_16BF, n, n, n));
 
     std::vector<hipblasLtMatmulHeuristicResult_t> all;
-    BLT(hipblaslt_ext::getAllAlgos(G.handle, hipblaslt_ext::GemmType::HIPBLASLT_GEMM, op, op, HIP_R_16BF, HIP_R_16BF,
+    BLT(hipblaslt_ext::getAllAlgos(G.handle, hipblaslt_ext::GemmType::HIPBLASLT_GEMM, op_a, op_b, HIP_R_16BF, HIP_R_16BF,
                                    HIP_R_16BF, HIP_R_16BF, HIPBLAS_COMPUTE_32F, all));
     for (auto &r : all) {
         size_t ws = 0;
