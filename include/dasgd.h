@@ -67,7 +67,10 @@ enum {
                                 whatever the caller enqueues on the main stream after this step's calls
                                 (the next forward/backward pass -- the paper's point: averaging hidden
                                 behind local work, Fig. 2 and Fig. 4).  The library's own kernels, which
-                                all saturate HBM, wait for a mean in flight instead of competing with it */
+                                all saturate HBM, wait for a mean in flight instead of competing with it.
+                                The mean is dispatched about 20 us behind the caller's next kernel, so
+                                that it fills the wave slots that kernel leaves free instead of taking
+                                them first (dasgd_set_side_stream_head_start in dasgd_diag.h) */
     DASGD_SCHED_SERIAL  = 1, /* everything on the main stream in program order (no overlap) */
     DASGD_SCHED_NO_AVERAGE_TIMING_ONLY = 2, /* timing floor: no snapshot and no mean are run, the
                                 merge reads whatever the slot holds.  RESULTS ARE MEANINGLESS. */
