@@ -629,6 +629,35 @@ __global__ void __launch_bounds__(64 * NW) all_groups(const RowPtrs p, const v4f
     }
 }
 
+// one wave, the W rows on W groups of 64/W lanes (a window is 64/W columns wide), sums by cross-lane exchange
+template <int WT>
+__global__ void __launch_bounds__(64) all_lanes(const RowPtrs p, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4,
+                                                float lr, float mo, float wd, float om, float inv_w)
+{
+    constexpr int G = 64 / WT;
+    const int r = threadIdx.x / G;
+    const unsigned c = blockIdx.x * G + threadIdx.x % G;
+    const bool in = c < row4;
+    v4f y = {0.f, 0.f, 0.f, 0.f};
+    if (in) {
+        v4f a = ld4<false>(A_old + c); arrived(a);
+        v4f xr = ld4<true>(p.x[r] + c); arrived(xr);
+        v4f vr = ld4<true>(p.v[r] + c); arrived(vr);
+        v4f gr = ld4<true>(p.g[r] + c); arrived(gr);
+        sgd4(xr, vr, gr, lr, mo, wd);
+        st4<true>(p.v[r] + c, vr);
+        st4<true>(p.x[r] + c, merge4(xr, a, om));
+        y = xr;
+    }
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1) {
+        v4f o;
+        o.x = __shfl_xor(y.x, off); o.y = __shfl_xor(y.y, off); o.z = __shfl_xor(y.z, off); o.w = __shfl_xor(y.w, off);
+        y = y + o;
+    }
+    if (in && r == 0) st4<false>(A_new + c, y * inv_w);
+}
+
 __global__ void k_fill(float *p, size_t n, unsigned seed, float scale)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -936,7 +965,8 @@ int main(int argc, char **argv)
             run("one wave walks the W rows, a row's loads one after the other", B_ALL, [&] { hipLaunchKernelGGL((all_walk<WT, false>), dim3(bpr), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
             run("one wave walks the W rows, a row's loads together", B_ALL, [&] { hipLaunchKernelGGL((all_walk<WT, true>), dim3(bpr), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
             run("2 waves per workgroup, W/2 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 2>), dim3(bpr), dim3(128), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
-            run("4 waves per workgroup, W/4 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 4>), dim3(bpr), dim3(256), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); });
+            run("4 waves per workgroup, W/4 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 4>), dim3(bpr), dim3(256), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("one wave, the W rows on W lane groups, cross-lane sums", B_ALL, [&] { hipLaunchKernelGGL((all_lanes<WT>), dim3((row4 + 64 / WT - 1) / (64 / WT)), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); });
             switch (W) { case 4: { ALL_VARIANTS(4) } break; case 8: { ALL_VARIANTS(8) } break; default: { ALL_VARIANTS(16) } break; }
 #undef ALL_VARIANTS
         }
