@@ -219,13 +219,15 @@ def run_oracle(cfg: Config, dtype: str = "f64", steps: Optional[int] = None, idx
         sigma_dev = wl.grad_sigma_vector(cfg, gen_device, idx_dev)
         stage = torch.empty((cfg.W, n), dtype=torch.float64 if dtype == "f64" else torch.float32,
                             pin_memory=torch.device(gen_device).type == "cuda")
+        stage_dev = torch.empty((cfg.W, n), dtype=stage.dtype, device=gen_device)     # widened there, copied once
 
     def grads(k: int, x: np.ndarray) -> np.ndarray:
         if quad is not None:
             return np.stack([quad.grad(torch.from_numpy(x[j]), k, j, idx=idx).numpy() for j in range(cfg.W)])
         if stage is not None:
             for j in range(cfg.W):
-                stage[j].copy_(wl.gradient(cfg, k, j, gen_device, idx=idx_dev, sigma=sigma_dev))
+                stage_dev[j].copy_(wl.gradient(cfg, k, j, gen_device, idx=idx_dev, sigma=sigma_dev))
+            stage.copy_(stage_dev)
             return stage.numpy()
         return np.stack([wl.gradient(cfg, k, j, "cpu", idx=idx, sigma=sigma).numpy() for j in range(cfg.W)]).astype(npdt)
 
