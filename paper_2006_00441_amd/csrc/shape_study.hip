@@ -458,6 +458,19 @@ __global__ void __launch_bounds__(64) ls_flat_order(v4f *__restrict__ x, v4f *__
     sgd4(xr, vr, gr, lr, mo, wd);
     st4<true>(x + i, xr); st4<true>(v + i, vr);
 }
+// loads one after the other; which of loads and stores are non-temporal
+template <bool LD_NT, bool ST_NT>
+__global__ void __launch_bounds__(64) ls_flat_hints(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, int64_t n4,
+                                                    float lr, float mo, float wd)
+{
+    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (i >= n4) return;
+    v4f xr = ld4<LD_NT>(x + i); arrived(xr);
+    v4f vr = ld4<LD_NT>(v + i); arrived(vr);
+    v4f gr = ld4<LD_NT>(g + i); arrived(gr);
+    sgd4(xr, vr, gr, lr, mo, wd);
+    st4<ST_NT>(x + i, xr); st4<ST_NT>(v + i, vr);
+}
 // two kilobytes per array and wave, the arrays one after the other
 template <int THREADS>
 __global__ void __launch_bounds__(THREADS) ls_flat_pairs(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, int64_t n4,
@@ -836,6 +849,9 @@ int main(int argc, char **argv)
         run("flat, 64 x 1, loads: x, then v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_order<1>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 64 x 1, loads: x and v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_order<2>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 64 x 1, loads: g, then v, then x", B_LS, [&] { hipLaunchKernelGGL((ls_flat_order<3>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
+        run("flat, 64 x 1, loads one after the other, non-temporal loads, plain stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<true, false>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
+        run("flat, 64 x 1, loads one after the other, plain loads, non-temporal stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<false, true>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
+        run("flat, 64 x 1, loads one after the other, plain loads and stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<false, false>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 64 x 2: x x, then v v, then g g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_pairs<64>), dim3((unsigned)(n4 / 128)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 128 x 1, loads: x, then v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_serial_wg<128>), dim3((unsigned)((n4 + 127) / 128)), dim3(128), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 256 x 1, loads: x, then v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_serial_wg<256>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
