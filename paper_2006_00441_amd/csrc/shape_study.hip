@@ -471,6 +471,31 @@ __global__ void __launch_bounds__(64) ls_flat_hints(v4f *__restrict__ x, v4f *__
     sgd4(xr, vr, gr, lr, mo, wd);
     st4<ST_NT>(x + i, xr); st4<ST_NT>(v + i, vr);
 }
+// the same through raw buffer loads and stores (one descriptor per row), whose cache-policy operand can be set
+// freely: bit 0 = sc0, bit 1 = nt, bit 4 = sc1 (the non-temporal builtins give nt alone)
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+template <int AUX_LD, int AUX_ST>
+__global__ void __launch_bounds__(64) ls_buf(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, unsigned ld4,
+                                             float lr, float mo, float wd)
+{
+    const unsigned c = blockIdx.x * 64 + threadIdx.x;
+    if (c >= ld4) return;
+    const size_t row = (size_t)blockIdx.y * ld4;
+    const int bytes = (int)(ld4 * 16u);
+    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(x + row), 0, bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(v + row), 0, bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void *)(g + row), 0, bytes, 0x00020000);
+    const int off = (int)(c * 16u);
+    v4u xu = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, AUX_LD);
+    v4f xr = __builtin_bit_cast(v4f, xu); arrived(xr);
+    v4u vu = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, AUX_LD);
+    v4f vr = __builtin_bit_cast(v4f, vu); arrived(vr);
+    v4u gu = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, AUX_LD);
+    v4f gr = __builtin_bit_cast(v4f, gu); arrived(gr);
+    sgd4(xr, vr, gr, lr, mo, wd);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, xr), rx, off, 0, AUX_ST);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, vr), rv, off, 0, AUX_ST);
+}
 // two kilobytes per array and wave, the arrays one after the other
 template <int THREADS>
 __global__ void __launch_bounds__(THREADS) ls_flat_pairs(v4f *__restrict__ x, v4f *__restrict__ v, const v4f *__restrict__ g, int64_t n4,
@@ -852,6 +877,19 @@ int main(int argc, char **argv)
         run("flat, 64 x 1, loads one after the other, non-temporal loads, plain stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<true, false>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 64 x 1, loads one after the other, plain loads, non-temporal stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<false, true>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 64 x 1, loads one after the other, plain loads and stores", B_LS, [&] { hipLaunchKernelGGL((ls_flat_hints<false, false>), dim3((unsigned)((n4 + 63) / 64)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
+#define LS_BUF(LD, ST, what) run("flat rows, raw buffer accesses, " what, B_LS, [&] { \
+            hipLaunchKernelGGL((ls_buf<LD, ST>), dim3((unsigned)((ld / 4 + 63) / 64), (unsigned)W), dim3(64), 0, 0, fx, fv, fg, (unsigned)(ld / 4), lr, mo, wd); })
+        LS_BUF(2, 2, "loads nt, stores nt");
+        LS_BUF(2, 3, "loads nt, stores sc0 nt");
+        LS_BUF(2, 18, "loads nt, stores sc1 nt");
+        LS_BUF(2, 19, "loads nt, stores sc0 sc1 nt");
+        LS_BUF(2, 17, "loads nt, stores sc0 sc1");
+        LS_BUF(3, 2, "loads sc0 nt, stores nt");
+        LS_BUF(18, 2, "loads sc1 nt, stores nt");
+        LS_BUF(19, 2, "loads sc0 sc1 nt, stores nt");
+        LS_BUF(19, 19, "loads sc0 sc1 nt, stores sc0 sc1 nt");
+        LS_BUF(0, 0, "plain");
+#undef LS_BUF
         run("flat, 64 x 2: x x, then v v, then g g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_pairs<64>), dim3((unsigned)(n4 / 128)), dim3(64), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 128 x 1, loads: x, then v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_serial_wg<128>), dim3((unsigned)((n4 + 127) / 128)), dim3(128), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
         run("flat, 256 x 1, loads: x, then v, then g", B_LS, [&] { hipLaunchKernelGGL((ls_flat_serial_wg<256>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, 0, fx, fv, fg, n4, lr, mo, wd); });
