@@ -549,7 +549,11 @@ def compare_algorithms(arena: Arena, steps: int, warmup: int):
     floor = out["local_steps_only"]
     return {"ms_per_step": {k: round(t, 4) for k, t in out.items()},
             "averaging_share": {k: round((t - floor) / t, 4) for k, t in out.items() if k != "local_steps_only"},
-            "note": "each step = bf16 8192^3 GEMM stand-in + the schedule's parameter work, W=%d replicas" % cfg.W}
+            "note": "each step = bf16 8192^3 GEMM stand-in + the schedule's parameter work, W=%d replicas" % cfg.W,
+            "paper_context": "the paper measures none of this: its Section 5.2 simulates a cluster (PALEO model, 256 workers on "
+                             "TITAN X GPUs, 8 per server on PCIe 3, 20 Gb Ethernet between servers, ResNet-50, local batch 64) and "
+                             "finds inter-worker aggregation at 45.9 % of the epoch time for Mini-batch SGD, 17.5 % for Local SGD "
+                             "(tau = 4) and 0 % for DaSGD; other hardware, another cost (network, not HBM): context, not a target"}
 
 
 def quadratic_period_maps(a, lr: float, momentum: float, xi: float, d: int):
