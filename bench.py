@@ -813,6 +813,12 @@ def main() -> int:
             f3 = measure(arena, max(20, min(args.steps, 100)), 5, fusion=pkg.FUSE_ALL)
             f3.pop("_run").close()
             out["fusion_all"] = brief(f3)
+            # what a long run settles into: past the step budget of the zero-copy reconstruction (500 steps at
+            # xi = 0.25) the default stores snapshots -- or, once the measured schedule is the serial one, takes the
+            # one-kernel step, which gives the same bits as store + mean
+            lr_ = measure(arena, 40, 520)
+            lr_.pop("_run").close()
+            out["after_500_steps"] = dict(brief(lr_), note="the library's defaults, 520 untimed steps first")
     arena.close()
     if args.cu_partition:
         del arena, streams, main_s, side_s

@@ -103,16 +103,25 @@ enum {
                                   the merge reads x, writes x */
     DASGD_FUSE_SNAPSHOT   = 1, /* when a snapshot AND a merge fall on the same step, the local step stores
                                   the new weights only into the snapshot and the merge reads them there */
-    DASGD_FUSE_STEP_MERGE = 2, /* default: when a merge is due at the step being taken (and d > 0), the local
+    DASGD_FUSE_STEP_MERGE = 2, /* when a merge is due at the step being taken (and d > 0), the local
                                   step applies it in the same pass (Eq. 2, both branches at once) and
                                   dasgd_merge only retires the average; otherwise as DASGD_FUSE_SNAPSHOT */
-    DASGD_FUSE_ALL        = 3  /* the mean is computed by the local-step kernel too (a workgroup updates a
+    DASGD_FUSE_ALL        = 3, /* the mean is computed by the local-step kernel too (a workgroup updates a
                                   window of columns of all W replicas and sums the new values through
                                   LDS): no snapshot, no mean kernel, nothing on the side stream;
                                   dasgd_average_begin and dasgd_merge only keep the books.  What one GPU
                                   can do when the average need not be a separate, overlappable operation.
                                   Needs the rows layout (see dasgd_local_step) for x, v and g, and d > 0;
                                   otherwise behaves as DASGD_FUSE_STEP_MERGE */
+    DASGD_FUSE_AUTO       = 4  /* default: DASGD_FUSE_STEP_MERGE, with the mean a kernel of its own that the
+                                  overlap schedule can put on the side stream -- except on steps where a
+                                  snapshot would have to be STORED (DASGD_SNAPSHOT_COPY, or
+                                  DASGD_SNAPSHOT_AUTO after its step budget or below its xi limit) while the
+                                  schedule in force is DASGD_SCHED_SERIAL (set, or chosen by
+                                  DASGD_SCHED_AUTO): the mean would run in line anyway, so those steps take
+                                  the DASGD_FUSE_ALL kernel (W = 2, 4, 8 or 16, rows layout, d > 0), which
+                                  gives the same bits as snapshot store + mean for 20+8/W instead of 28+8/W
+                                  bytes per replica-parameter.  Results never depend on it */
 };
 
 /* Where the average finds the weights it averages (dasgd_set_snapshot). */
@@ -131,7 +140,7 @@ enum {
                                      scales with 1/xi.  The library's own kernels wait for the mean; a
                                      caller whose OWN kernels write x between two steps (clipping,
                                      loading a checkpoint) must first wait for side_stream, or use the
-                                     copy mode.  Taken when: schedule OVERLAP, SERIAL or AUTO; fusion level 2;
+                                     copy mode.  Taken when: schedule OVERLAP, SERIAL or AUTO; fusion level 2 or AUTO;
                                      and either no merge falls on the step or xi >= 1/8 (any memory
                                      layout: the mean finds the live weights through row pointers or through
                                      the record table).  Otherwise the copy is made */
@@ -139,7 +148,9 @@ enum {
                                      the context (none for xi < 1/8), stored snapshots from then on, so
                                      that the accuracy statement at the top of this file holds whatever
                                      the run length: the reconstruction's extra rounding is spent while
-                                     the accumulated error is still small */
+                                     the accumulated error is still small.  (With DASGD_FUSE_AUTO and the
+                                     serial schedule "stored snapshots" become the one-kernel step, which
+                                     gives the same bits and stores none) */
 };
 
 /* Kernel kinds, for dasgd_profile_read and dasgd_band (dasgd_diag.h). */

@@ -21,7 +21,7 @@ K_STEP_MEAN, K_STEP_MEAN_MERGE, K_MEAN_RECONSTRUCT = 7, 8, 9
 SNAPSHOT_COPY, SNAPSHOT_ZERO_COPY, SNAPSHOT_AUTO = 0, 1, 2
 ADDR_RECORDS, ADDR_ROWS, ADDR_ROWS_XV = 0, 1, 2
 MAP_ROWS, MAP_MEAN, MAP_MEAN_RUNS = 0, 1, 2
-FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE, FUSE_ALL = 0, 1, 2, 3
+FUSE_NONE, FUSE_SNAPSHOT, FUSE_STEP_MERGE, FUSE_ALL, FUSE_AUTO = 0, 1, 2, 3, 4
 KERNEL_NAMES = {K_LOCAL_STEP: "local_step", K_LOCAL_STEP_SNAP: "local_step_snapshot",
                 K_MEAN: "mean", K_MERGE: "merge", K_LOCAL_STEP_TO_SNAP: "local_step_to_snapshot",
                 K_STEP_MERGE: "step_merge", K_STEP_SNAP_MERGE: "step_snapshot_merge",

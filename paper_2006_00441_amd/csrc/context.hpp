@@ -89,7 +89,7 @@ struct dasgd_ctx {
     int64_t P = 0;
     float lr = 0, momentum = 0, wd = 0, xi = 0.25f;
     int schedule = DASGD_SCHED_AUTO;
-    int fusion = DASGD_FUSE_STEP_MERGE;
+    int fusion = DASGD_FUSE_AUTO;
     int snapshot = DASGD_SNAPSHOT_AUTO;
     int slots = 1;
     size_t side_min_bytes = (size_t)64 << 20;   // means that move less than this run on the main stream

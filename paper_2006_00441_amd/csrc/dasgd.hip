@@ -64,7 +64,7 @@ int dasgd_set_side_stream_threshold(dasgd_ctx *c, size_t bytes)
 
 int dasgd_set_fusion(dasgd_ctx *c, int fusion)
 {
-    if (!c || fusion < DASGD_FUSE_NONE || fusion > DASGD_FUSE_ALL) return DASGD_EINVAL;
+    if (!c || fusion < DASGD_FUSE_NONE || fusion > DASGD_FUSE_AUTO) return DASGD_EINVAL;
     if (!c->pending.empty() || begin_due(c)) return DASGD_ESTATE;
     c->fusion = fusion;
     return DASGD_OK;
@@ -304,14 +304,16 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
     const int sched = effective_schedule(c);
     c->sched_now = sched;
     const bool snap = snap_step && sched != DASGD_SCHED_NO_AVERAGE_TIMING_ONLY;
+    // DASGD_FUSE_AUTO is level 2, raised to level 3 on the steps where that changes no bit (see below)
+    const int fusion = c->fusion == DASGD_FUSE_AUTO ? DASGD_FUSE_STEP_MERGE : c->fusion;
     // fold the merge into this kernel?  (not for d == 0: that merge needs the mean of this step's own output)
-    const bool fold = merge_follows && c->d > 0 && c->fusion >= DASGD_FUSE_STEP_MERGE;
+    const bool fold = merge_follows && c->d > 0 && fusion >= DASGD_FUSE_STEP_MERGE;
     int mode = kStoreX;
-    if (snap) mode = (merge_follows && !fold && c->fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
+    if (snap) mode = (merge_follows && !fold && fusion >= DASGD_FUSE_SNAPSHOT) ? kStoreS : kStoreXS;
     // zero-copy snapshot: store none, let the mean read x (see DASGD_SNAPSHOT_*)
     const bool zc_wanted = c->snapshot == DASGD_SNAPSHOT_ZERO_COPY ||
                            (c->snapshot == DASGD_SNAPSHOT_AUTO && k < zero_copy_budget(c->xi));
-    const bool zc = snap && zc_wanted && c->fusion == DASGD_FUSE_STEP_MERGE &&
+    const bool zc = snap && zc_wanted && fusion == DASGD_FUSE_STEP_MERGE &&
                     (sched == DASGD_SCHED_OVERLAP || sched == DASGD_SCHED_SERIAL) &&
                     (fold ? c->xi >= 0.125f : !merge_follows);
     if (zc) mode = kStoreX;
@@ -353,7 +355,12 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         if (phase_mark) HIPCHK(c, hipEventRecord(phase_mark, c->main_s));
         if (fold) A = avg_ptr(c, c->pending.front().slot);
         const bool row_kernels = c->xv_rows && g_rows_new;
-        all = c->fusion == DASGD_FUSE_ALL && c->d > 0 && row_kernels && snap;
+        // A snapshot that would have to be stored (no zero-copy on this step) under a schedule that runs the
+        // mean in line anyway: the all-in-one kernel gives the same bits as store + mean (all fusion levels
+        // agree with stored snapshots) for 20+8/W instead of 28+8/W bytes per replica-parameter.
+        const bool raise = c->fusion == DASGD_FUSE_AUTO && !zc && sched == DASGD_SCHED_SERIAL &&
+                           (c->W == 2 || c->W == 4 || c->W == 8 || c->W == 16);
+        all = (fusion == DASGD_FUSE_ALL || raise) && c->d > 0 && row_kernels && snap;
         const int kid = all ? (fold ? DASGD_K_STEP_MEAN_MERGE : DASGD_K_STEP_MEAN)
                       : fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP

@@ -64,10 +64,10 @@ def test_create_validates_arguments():
     assert o.schedule_in_use()[:2] == (pkg.SCHED_AUTO, False)
     o.set_schedule(pkg.SCHED_SERIAL)
     assert o.schedule_in_use()[:2] == (pkg.SCHED_SERIAL, True)
-    for f in (-1, 4):
+    for f in (-1, 5):
         with pytest.raises(DasgdError):
             o.set_fusion(f)
-    for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL):
+    for f in (pkg.FUSE_NONE, pkg.FUSE_SNAPSHOT, pkg.FUSE_STEP_MERGE, pkg.FUSE_ALL, pkg.FUSE_AUTO):
         o.set_fusion(f)
     for m in (-1, 3):
         with pytest.raises(DasgdError):

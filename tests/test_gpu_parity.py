@@ -773,10 +773,49 @@ def test_snapshot_auto_switches_to_stored_snapshots_after_its_budget():
     for _ in range(cfg.steps):
         run.step()
     x = run.weights()
-    n_recon, n_copy = run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2], run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2]
+    n_recon = run.opt.profile_read(pkg.K_MEAN_RECONSTRUCT)[2]
+    # past the budget a snapshot is stored, or -- once the measured schedule has settled on serial -- the
+    # one-kernel step is taken, which gives the same bits
+    n_copy = run.opt.profile_read(pkg.K_STEP_SNAP_MERGE)[2] + run.opt.profile_read(pkg.K_STEP_MEAN_MERGE)[2]
     run.close()
     assert n_recon == 125 - 2 and n_copy == 35, (n_recon, n_copy)      # (the first two steps have nothing to merge)
     assert max_scaled_error(cfg, x, run_oracle(cfg, "f64")) <= TOL
+
+
+@pytest.mark.parametrize("tau,d,W", [(1, 2, 8), (4, 2, 16), (2, 4, 4), (1, 1, 2)])
+def test_default_fusion_takes_the_one_kernel_step_only_where_it_changes_no_bit(tau, d, W):
+    """DASGD_FUSE_AUTO: where a snapshot would be stored and the schedule is serial, the all-in-one kernel runs
+    instead (same bits as store + mean); under the overlap schedule, with the zero-copy snapshot, or for
+    other W it does not."""
+    import paper_2006_00441_amd as pkg
+    cfg = small(tau=tau, d=d, W=W, steps=4 * tau + 2 * d + 7, params=custom_param_set(SETS["matrix"]))
+
+    def go(**kw):
+        run = GpuRun(cfg, **kw)
+        run.opt.profile(1, 4096)
+        for _ in range(cfg.steps):
+            run.step()
+        x = torch.from_numpy(run.weights())
+        n = {name: run.opt.profile_read(kid)[2] for kid, name in pkg.KERNEL_NAMES.items()}
+        run.close()
+        return x, n
+
+    ref, n_ref = go(fusion=pkg.FUSE_STEP_MERGE, snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_SERIAL)
+    x, n = go(snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_SERIAL)
+    one_kernel = n["step_mean"] + n["step_mean_merge"]
+    assert torch.equal(x, ref) and one_kernel == cfg.steps // tau and n["mean"] == 0 and n["local_step_snapshot"] + n["step_snapshot_merge"] == 0, n
+    assert n_ref["step_mean"] + n_ref["step_mean_merge"] == 0 and n_ref["mean"] == cfg.steps // tau, n_ref
+    x, n = go(snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_OVERLAP)
+    assert torch.equal(x, ref) and n["step_mean"] + n["step_mean_merge"] == 0 and n["mean"] == cfg.steps // tau, n
+    x, n = go(snapshot=pkg.SNAPSHOT_ZERO_COPY, schedule=pkg.SCHED_SERIAL)
+    assert n["step_mean"] + n["step_mean_merge"] == 0, n
+    odd = small(tau=tau, d=d, W=3, steps=cfg.steps, params=custom_param_set(SETS["matrix"]))
+    run = GpuRun(odd, snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_SERIAL)
+    run.opt.profile(1, 4096)
+    for _ in range(odd.steps):
+        run.step()
+    assert run.opt.profile_read(pkg.K_STEP_MEAN)[2] + run.opt.profile_read(pkg.K_STEP_MEAN_MERGE)[2] == 0
+    run.close()
 
 
 @pytest.mark.timeout(600)
