@@ -667,6 +667,41 @@ __global__ void __launch_bounds__(64 * NW) all_groups(const RowPtrs p, const v4f
     }
 }
 
+// W waves per workgroup, one row each, y through LDS -- but no barrier behind the loads: every wave announces
+// itself on an LDS counter and leaves; the last to arrive adds the W values and stores the average
+template <int WT>
+__global__ void __launch_bounds__(64 * WT) all_last_arriver(const RowPtrs p, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4,
+                                                           float lr, float mo, float wd, float om, float inv_w)
+{
+    __shared__ v4f part[WT][64];
+    __shared__ unsigned count;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
+    if (threadIdx.x == 0) count = 0;
+    __syncthreads();                                   // before any memory latency: costs next to nothing
+    const unsigned c = blockIdx.x * 64 + l;
+    if (c < row4) {
+        v4f a = ld4<false>(A_old + c); arrived(a);
+        v4f xr = ld4<true>(p.x[w] + c); arrived(xr);
+        v4f vr = ld4<true>(p.v[w] + c); arrived(vr);
+        v4f gr = ld4<true>(p.g[w] + c); arrived(gr);
+        sgd4(xr, vr, gr, lr, mo, wd);
+        st4<true>(p.v[w] + c, vr);
+        st4<true>(p.x[w] + c, merge4(xr, a, om));
+        part[w][l] = xr;
+    }
+    __threadfence_block();
+    unsigned before = 0;
+    if (l == 0) before = atomicAdd(&count, 1u);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before != WT - 1) return;
+    __threadfence_block();
+    if (c < row4) {
+        v4f q[WT];
+#pragma unroll
+        for (int k = 0; k < WT; ++k) q[k] = part[k][l];
+        st4<false>(A_new + c, tree_sum<0, WT>(q) * inv_w);
+    }
+}
 // one wave, the W rows on W groups of 64/W lanes (a window is 64/W columns wide), sums by cross-lane exchange
 template <int WT>
 __global__ void __launch_bounds__(64) all_lanes(const RowPtrs p, const v4f *__restrict__ A_old, v4f *__restrict__ A_new, unsigned row4,
@@ -1020,6 +1055,7 @@ int main(int argc, char **argv)
             run("one wave walks the W rows, a row's loads together", B_ALL, [&] { hipLaunchKernelGGL((all_walk<WT, true>), dim3(bpr), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
             run("2 waves per workgroup, W/2 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 2>), dim3(bpr), dim3(128), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
             run("4 waves per workgroup, W/4 rows each, LDS", B_ALL, [&] { hipLaunchKernelGGL((all_groups<WT, 4>), dim3(bpr), dim3(256), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
+            run("W waves per workgroup, LDS, the last wave to arrive sums (no barrier behind the loads)", B_ALL, [&] { hipLaunchKernelGGL((all_last_arriver<WT>), dim3(bpr), dim3(64 * WT), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); }); \
             run("one wave, the W rows on W lane groups, cross-lane sums", B_ALL, [&] { hipLaunchKernelGGL((all_lanes<WT>), dim3((row4 + 64 / WT - 1) / (64 / WT)), dim3(64), 0, 0, into_flat, A, A2, row4, lr, mo, wd, om, 1.0f / W); });
             switch (W) { case 4: { ALL_VARIANTS(4) } break; case 8: { ALL_VARIANTS(8) } break; default: { ALL_VARIANTS(16) } break; }
 #undef ALL_VARIANTS
