@@ -837,8 +837,12 @@ def main() -> int:
             a = Arena(cfg, lay)
             mm = measure(a, 40, 5)
             mm.pop("_run").close()
-            a.close()
             layouts[cfg.name][lay] = brief(mm, cfg.name, lay)
+            if lay == "separate":           # the one-kernel step through the record table (fusion level 3)
+                mm = measure(a, 40, 5, fusion=pkg.FUSE_ALL)
+                mm.pop("_run").close()
+                layouts[cfg.name]["separate_fusion_all"] = brief(mm, cfg.name, lay)
+            a.close()
         for name, steps in (("quadratic", 200), ("resnet50_w8", 80), ("resnet50_w16", 240)):
             c = wl.get_config(name)
             a = Arena(c, "matrix")
@@ -885,8 +889,12 @@ def main() -> int:
                     a = Arena(c, lay)
                     mm = measure(a, 240, 10)
                     mm.pop("_run").close()
-                    a.close()
                     layouts[name][lay] = brief(mm, name, lay)
+                    if lay == "separate":
+                        mm = measure(a, 240, 10, fusion=pkg.FUSE_ALL)
+                        mm.pop("_run").close()
+                        layouts[name]["separate_fusion_all"] = brief(mm, name, lay)
+                    a.close()
         # the xi / d / tau study on the quadratic, compact (all columns: bench.py --sweep)
         sw = sweep_quadratic()
         out["parameter_study"] = {

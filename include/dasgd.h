@@ -111,15 +111,16 @@ enum {
                                   LDS): no snapshot, no mean kernel, nothing on the side stream;
                                   dasgd_average_begin and dasgd_merge only keep the books.  What one GPU
                                   can do when the average need not be a separate, overlappable operation.
-                                  Needs the rows layout (see dasgd_local_step) for x, v and g, and d > 0;
-                                  otherwise behaves as DASGD_FUSE_STEP_MERGE */
+                                  Needs d > 0 and either W = 2, 4, 8 or 16 (any memory layout) or the rows
+                                  layout (see dasgd_local_step) for x, v and g (any W <= 32); otherwise
+                                  behaves as DASGD_FUSE_STEP_MERGE */
     DASGD_FUSE_AUTO       = 4  /* default: DASGD_FUSE_STEP_MERGE, with the mean a kernel of its own that the
                                   overlap schedule can put on the side stream -- except on steps where a
                                   snapshot would have to be STORED (DASGD_SNAPSHOT_COPY, or
                                   DASGD_SNAPSHOT_AUTO after its step budget or below its xi limit) while the
                                   schedule in force is DASGD_SCHED_SERIAL (set, or chosen by
                                   DASGD_SCHED_AUTO): the mean would run in line anyway, so those steps take
-                                  the DASGD_FUSE_ALL kernel (W = 2, 4, 8 or 16, rows layout, d > 0), which
+                                  the DASGD_FUSE_ALL kernel (W = 2, 4, 8 or 16, d > 0; any memory layout), which
                                   gives the same bits as snapshot store + mean for 20+8/W instead of 28+8/W
                                   bytes per replica-parameter.  Results never depend on it */
 };

@@ -360,7 +360,11 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         // agree with stored snapshots) for 20+8/W instead of 28+8/W bytes per replica-parameter.
         const bool raise = c->fusion == DASGD_FUSE_AUTO && !zc && sched == DASGD_SCHED_SERIAL &&
                            (c->W == 2 || c->W == 4 || c->W == 8 || c->W == 16);
-        all = (fusion == DASGD_FUSE_ALL || raise) && c->d > 0 && row_kernels && snap;
+        const bool pow2_w = c->W == 2 || c->W == 4 || c->W == 8 || c->W == 16;
+        const uint64_t rec_blocks = (uint64_t)c->lay.n_pieces << kPieceLog;
+        // (through the record table the one-kernel step exists for W = 2, 4, 8, 16 only)
+        all = (fusion == DASGD_FUSE_ALL || raise) && c->d > 0 && snap &&
+              (row_kernels || (pow2_w && rec_blocks <= 0x7fffffffu));
         const int kid = all ? (fold ? DASGD_K_STEP_MEAN_MERGE : DASGD_K_STEP_MEAN)
                       : fold ? (mode == kStoreX ? DASGD_K_STEP_MERGE : DASGD_K_STEP_SNAP_MERGE)
                       : mode == kStoreX ? DASGD_K_LOCAL_STEP
@@ -370,7 +374,26 @@ int dasgd_local_step(dasgd_ctx *c, const float *const *g)
         rc = prof_open(c, kid, c->main_s, &rec);
         if (rc != DASGD_OK) return rc;
         const unsigned row4 = (unsigned)(c->P / 4);
-        if (all) {
+        if (all && !row_kernels) {
+            const Rec *recs = reinterpret_cast<const Rec *>(c->ws + c->lay.recs);
+            const float *const *gp = reinterpret_cast<const float *const *>(c->ws + c->lay.gp[g_buf]);
+            const dim3 agrid((unsigned)rec_blocks);
+            const float inv_w = 1.0f / (float)c->W;
+#define DASGD_LAUNCH_RECORDS(WT)                                                                                \
+    do {                                                                                                        \
+        if (fold) hipLaunchKernelGGL((k_step_all_records<WT, true>), agrid, dim3(kWave * WT), 0, c->main_s, recs, (unsigned)c->lay.n_pieces, \
+                                     (unsigned)rec_blocks, gp, c->n_tensors, A, avg_ptr(c, slot), c->lr, c->momentum, c->wd, om, inv_w); \
+        else      hipLaunchKernelGGL((k_step_all_records<WT, false>), agrid, dim3(kWave * WT), 0, c->main_s, recs, (unsigned)c->lay.n_pieces, \
+                                     (unsigned)rec_blocks, gp, c->n_tensors, A, avg_ptr(c, slot), c->lr, c->momentum, c->wd, om, inv_w); \
+    } while (0)
+            switch (c->W) {
+            case 2:  DASGD_LAUNCH_RECORDS(2);  break;
+            case 4:  DASGD_LAUNCH_RECORDS(4);  break;
+            case 8:  DASGD_LAUNCH_RECORDS(8);  break;
+            default: DASGD_LAUNCH_RECORDS(16); break;
+            }
+#undef DASGD_LAUNCH_RECORDS
+        } else if (all) {
             const dim3 agrid((row4 + kWave - 1) / kWave);
             const v4f *Ao = reinterpret_cast<const v4f *>(A);
             v4f *An = reinterpret_cast<v4f *>(avg_ptr(c, slot));

@@ -480,6 +480,86 @@ k_step_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slo
     }
 }
 
+// Everything of one iteration in one pass, records addressing: the W replicas' copies of a 256-float block
+// on the W wavefronts of a workgroup (grid = slots workgroups; workgroup q handles block q mod 16 of piece
+// q div 16).  Wavefront j does replica j's local step and merge exactly as k_step_records does (128-bit
+// accesses where that replica's addresses allow, 32-bit ones otherwise), leaves its y in LDS by position in
+// the block, and after the barrier wavefront 0 adds the W values in tree order and stores the average.
+// Same operations in the same order as the separate kernels (identical bits).  W = WT.
+template <int LO, int HI> __device__ __forceinline__ float tree_sum1(const float *r) {
+    if constexpr (HI - LO == 1) return r[LO];
+    else {
+        constexpr int MID = LO + (HI - LO + 1) / 2;
+        return tree_sum1<LO, MID>(r) + tree_sum1<MID, HI>(r);
+    }
+}
+template <int WT, bool MERGE>
+__global__ void __launch_bounds__(kWave * WT)
+k_step_all_records(const Rec *__restrict__ recs, unsigned recs_per_row, unsigned slots, const float *const *__restrict__ gp, int n_tensors,
+                   const float *__restrict__ A_old, float *__restrict__ A_new, float lr, float momentum, float wd, float om, float inv_w)
+{
+    __shared__ __attribute__((aligned(16))) float part[WT][256];
+    const unsigned q = blockIdx.x;
+    if (q >= slots) return;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), l = threadIdx.x % kWave;
+    const unsigned piece = q >> kPieceLog, first = (q & ((1u << kPieceLog) - 1u)) * 256u;
+    const unsigned len = recs[piece].len, aoff = recs[piece].aoff;      // replica 0's: the same for every replica
+    if (first >= len) return;                                           // (uniform over the workgroup)
+    const Rec r = recs[(size_t)w * recs_per_row + piece];
+    gf32 *x = (gf32 *)r.x, *v = (gf32 *)r.v;
+    cgf32 *g = (cgf32 *)(gp[(size_t)w * n_tensors + r.tensor] + r.goff);
+    cgf32 *a = MERGE ? (cgf32 *)(A_old + aoff) : nullptr;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(r.x) | reinterpret_cast<uintptr_t>(r.v) | (uintptr_t)g | (uintptr_t)a) & 15u) == 0;
+    if (aligned) {
+        const unsigned c = first / 4 + l, n4 = len >> 2;
+        if (c < n4) {
+            v4f av = {0.f, 0.f, 0.f, 0.f};
+            if (MERGE) { av = *((cgv4f *)a + c); arrived(av); }
+            v4f xr = gld4((cgv4f *)x + c); arrived(xr);
+            v4f vr = gld4((cgv4f *)v + c); arrived(vr);
+            v4f gr = gld4((cgv4f *)g + c); arrived(gr);
+            sgd4(xr, vr, gr, lr, momentum, wd);
+            gst4((gv4f *)v + c, vr);
+            gst4((gv4f *)x + c, MERGE ? merge4(xr, av, om) : xr);
+            *reinterpret_cast<v4f *>(&part[w][4 * l]) = xr;
+        } else if (c == n4) {
+            for (unsigned e = n4 * 4; e < len; ++e) {
+                float xs = x[e], vs = v[e];
+                sgd1(xs, vs, g[e], lr, momentum, wd);
+                v[e] = vs;
+                x[e] = MERGE ? merge1(xs, a[e], om) : xs;
+                part[w][e - first] = xs;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned e = first + k * kWave + l;
+            if (e < len) {
+                float xs = x[e], vs = v[e];
+                sgd1(xs, vs, g[e], lr, momentum, wd);
+                v[e] = vs;
+                x[e] = MERGE ? merge1(xs, a[e], om) : xs;
+                part[w][k * kWave + l] = xs;
+            }
+        }
+    }
+    __syncthreads();
+    if (w == 0) {
+        gf32 *out = (gf32 *)(A_new + aoff);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned e = first + k * kWave + l;
+            if (e < len) {
+                float p[WT];
+#pragma unroll
+                for (int j = 0; j < WT; ++j) p[j] = part[j][k * kWave + l];
+                out[e] = tree_sum1<0, WT>(p) * inv_w;
+            }
+        }
+    }
+}
+
 // Delayed merge, records addressing.  FROM_S: the value after the local step is read from the snapshot.
 template <bool FROM_S>
 __global__ void __launch_bounds__(kWave)
