@@ -19,7 +19,7 @@ TOL = 1e-5      # bound on |x_gpu - x_oracle| / parameter scale, per tensor, who
 
 # ------------------------------------------------------------------------------------------------
 # GPU side
-class GpuRun:
+class DeviceRun:
     """Device state of one configuration bound to a library context.
 
     layout "arena": x, v, g each one W x P allocation, rows back to back; tensors are views at the
@@ -181,10 +181,10 @@ class GpuRun:
 
 
 def run_gpu(cfg: Config, steps: Optional[int] = None, layout: str = "arena", schedule: Optional[int] = None,
-            observer: Optional[Callable[[int, GpuRun], None]] = None, idx: Optional[torch.Tensor] = None,
+            observer: Optional[Callable[[int, DeviceRun], None]] = None, idx: Optional[torch.Tensor] = None,
             xi: Optional[float] = None, fusion: Optional[int] = None, snapshot: Optional[int] = None) -> np.ndarray:
     """Run cfg on the GPU through the C ABI; returns the final weights [W, P] (or at idx)."""
-    run = GpuRun(cfg, layout=layout, schedule=schedule, xi=xi, fusion=fusion, snapshot=snapshot)
+    run = DeviceRun(cfg, layout=layout, schedule=schedule, xi=xi, fusion=fusion, snapshot=snapshot)
     try:
         for k in range(cfg.steps if steps is None else steps):
             run.step()

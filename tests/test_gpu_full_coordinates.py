@@ -12,7 +12,7 @@ import pytest
 import torch
 
 import workloads as wl
-from harness import TOL, GpuRun, max_scaled_error, run_oracle
+from harness import TOL, DeviceRun, max_scaled_error, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +43,7 @@ def gpu_checkpoints(name):
         _gpu[name] = {}
         for layout, which in CHECKPOINTS[name].items():
             cps = [cfg.steps] if which == "final" else sorted({1, cfg.tau + cfg.d, cfg.steps // 2, cfg.steps})
-            run = GpuRun(cfg, layout=layout, side_threshold=None)       # the library's defaults, as the benchmark runs it
+            run = DeviceRun(cfg, layout=layout, side_threshold=None)       # the library's defaults, as the benchmark runs it
             snaps = {}
             for k in range(cfg.steps):
                 run.step()

@@ -9,7 +9,7 @@ import torch
 
 import workloads as wl
 from workloads.shapes import custom_param_set
-from harness import TOL, GpuRun, max_scaled_error, run_gpu, run_oracle, sample_indices
+from harness import TOL, DeviceRun, max_scaled_error, run_gpu, run_oracle, sample_indices
 
 pytestmark = pytest.mark.gpu
 
@@ -51,7 +51,7 @@ def test_local_step_kernel(layout, pset):
     import oracle
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1000, d=0, W=3, steps=3, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg, layout=layout)
+    run = DeviceRun(cfg, layout=layout)
     want = pkg.ADDR_RECORDS if (pset == "table" or layout == "separate") else pkg.ADDR_ROWS
     assert run.opt.addressing() == want                 # (before any gradient table has been seen)
     x = run.weights().astype(np.float64); v = np.zeros_like(x)
@@ -72,7 +72,7 @@ def test_mean_kernel(W, pset):
     """The W-way mean of the snapshot equals the oracle's mean of the post-update weights."""
     import oracle
     cfg = small(tau=1, d=3, W=W, steps=1, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     run.step()                                    # launches an average, merges nothing (d=3)
     y = run.weights()
     A = run.pending_average(0)
@@ -108,7 +108,7 @@ def test_merge_kernel(layout, xi, pset):
                                          ("rows_g_separate", "matrix"), ("rows", "matrix_tiny")])
 def test_small_runs_match_oracle(tau, d, W, layout, pset):
     cfg = small(tau=tau, d=d, W=W, steps=3 * tau + 2 * d + 9, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg, layout=layout)
+    run = DeviceRun(cfg, layout=layout)
     for _ in range(cfg.steps):
         run.step()
     x = run.weights()
@@ -159,7 +159,7 @@ def test_schedules_give_identical_results(pset, fusion):
     assert np.array_equal(run_gpu(cfg, schedule=pkg.SCHED_OVERLAP, fusion=fusion),
                           run_gpu(cfg, schedule=pkg.SCHED_SERIAL, fusion=fusion))
     # the library's own default keeps so small a mean on the main stream: same bits again
-    run = GpuRun(cfg, fusion=fusion, side_threshold=None)
+    run = DeviceRun(cfg, fusion=fusion, side_threshold=None)
     for _ in range(cfg.steps):
         run.step()
     assert np.array_equal(run.weights(), run_gpu(cfg, fusion=fusion))
@@ -173,7 +173,7 @@ def test_learning_rate_and_gradient_table_changes(pset):
     addressing takes like any other) against the oracle."""
     import oracle
     cfg = small(tau=2, d=1, W=4, steps=14, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     alt = [torch.zeros(cfg.W, cfg.P + (8 if i % 3 == 2 else 0), device=run.dev)[:, :cfg.P] for i in range(6)]
     off = cfg.params.offsets
     w0 = wl.init_weights(cfg).numpy()
@@ -260,7 +260,7 @@ def test_replicas_contract_at_full_size():
     """Property that holds at any size (Eq. 2, second branch): with identical gradients on every
     worker all replicas stay bit-identical through local steps, averages and merges."""
     cfg = wl.get_config("resnet50_w8").scaled(steps=6)
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     for k in range(cfg.steps):
         with torch.cuda.stream(run.main):
             g0 = wl.gradient(cfg, k, 0, run.dev, sigma=run.sigma)
@@ -280,7 +280,7 @@ def test_minibatch_sgd_on_the_same_kernels():
     the same trajectory) and (b) the library's own d=0, tau=1, xi=0 run."""
     import oracle
     base = small(tau=1000, d=0, W=4, steps=12, params=custom_param_set(SETS["matrix"]))
-    run = GpuRun(base)
+    run = DeviceRun(base)
     gbar = torch.zeros(base.P, device=run.dev)
     off = base.params.offsets
     bcast = [gbar[off[t]:off[t + 1]].data_ptr() for _ in range(base.W) for t in range(base.params.n_tensors)]
@@ -310,7 +310,7 @@ def one_cycle(k, K, lo=0.01, hi=0.1):
 def test_parameter_sweep_quadratic(xi, tau, d):
     import oracle
     cfg = wl.get_config("quadratic").scaled(params=wl.flat_param_set(2 * 4096 + 8), tau=tau, d=d, xi=xi, steps=30)
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     q = wl.QuadraticProblem.build(cfg, "cpu")
     ref = oracle.Oracle(cfg.W, cfg.P, d, tau, cfg.lr, cfg.momentum, cfg.wd, np.zeros(cfg.P), xi=xi, dtype="f64")
     for k in range(cfg.steps):
@@ -377,7 +377,7 @@ def test_many_replicas(W):
 def test_profile_counts_and_times_launches():
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=8, steps=12, params=custom_param_set(SETS["matrix"]))
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     run.opt.profile(2, 100)
     for _ in range(cfg.steps):
         run.step()
@@ -403,7 +403,7 @@ def test_zero_copy_snapshot_with_reconstruction(tau, d, W, xi, layout, pset):
     copy path in the last bits; both stay within the tolerance of the oracle."""
     import paper_2006_00441_amd as pkg
     cfg = small(tau=tau, d=d, W=W, xi=xi, steps=40, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg, layout=layout)
+    run = DeviceRun(cfg, layout=layout)
     run.opt.profile(1, 1000)
     for _ in range(cfg.steps):
         run.step()
@@ -432,7 +432,7 @@ def test_zero_copy_snapshot_is_exact_without_coinciding_merge(tau, d, W):
 def test_zero_copy_falls_back_to_the_copy_for_small_xi():
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=4, xi=0.05, steps=12, params=custom_param_set(SETS["matrix"]))
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     run.opt.profile(1, 1000)
     for _ in range(cfg.steps):
         run.step()
@@ -468,7 +468,7 @@ def test_quadratic_closed_form_on_gpu(xi, tau, d):
     from oracle_pins import quadratic_mean_closed_form
     K = 60
     cfg = wl.get_config("quadratic").scaled(params=wl.flat_param_set(4096 + 8), tau=tau, d=d, xi=xi, steps=K)
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     run.quad = wl.QuadraticProblem.build(cfg, run.dev, noise=False)
     for _ in range(K):
         run.step()
@@ -499,7 +499,7 @@ def test_largest_problem_that_fits(P):
                     init="normal", init_std=0.02, grad_std=1e-3)
     idx = sample_indices(cfg)
     ref = run_oracle(cfg, "f64", idx=idx)
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     assert run.opt.addressing() == pkg_mod().ADDR_ROWS
     run.opt.profile(1, 64)
     for _ in range(cfg.steps):
@@ -537,7 +537,7 @@ def test_band_length_never_changes_results(W, numel, layout, fusion, snapshot, t
     cfg = small(tau=tau, d=d, W=W, steps=24, params=custom_param_set(numel))
     outs = {}
     for band in (-1, 0, 1, 3, 8, 11):
-        run = GpuRun(cfg, layout=layout, fusion=fusion, snapshot=snapshot)
+        run = DeviceRun(cfg, layout=layout, fusion=fusion, snapshot=snapshot)
         run.opt.set_band(band)
         for _ in range(cfg.steps):
             run.step()
@@ -551,7 +551,7 @@ def test_band_length_never_changes_results(W, numel, layout, fusion, snapshot, t
 def test_band_measurement_settles_without_blocking():
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=1, W=8, steps=40, params=custom_param_set([2**20, 2**18 + 64, 512]))
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     assert run.opt.band(pkg.K_STEP_MERGE) == (-1, False)
     for k in range(cfg.steps):
         run.step()
@@ -582,7 +582,7 @@ def test_full_size_overlap_with_foreign_work_equals_serial(schedule_name):
     outs = {}
     for name in (schedule_name, "SCHED_SERIAL"):
         snap = pkg.SNAPSHOT_COPY if schedule_name == "SCHED_OVERLAP_FREE" else pkg.SNAPSHOT_ZERO_COPY
-        run = GpuRun(cfg, schedule=getattr(pkg, name), snapshot=snap)
+        run = DeviceRun(cfg, schedule=getattr(pkg, name), snapshot=snap)
         with torch.cuda.stream(run.main):
             a = torch.randn(4096, 4096, device=run.dev, dtype=torch.bfloat16)
             c = torch.empty_like(a)
@@ -653,7 +653,7 @@ def test_serial_steps_replay_from_a_hip_graph():
     period, replays = 2 * 4, 4                       # slots = 2: any multiple of 2 steps closes the rotation
 
     def fresh():
-        run = GpuRun(cfg, schedule=pkg.SCHED_SERIAL, side_threshold=None)
+        run = DeviceRun(cfg, schedule=pkg.SCHED_SERIAL, side_threshold=None)
         run.opt.set_band(0)
         run.fill_gradients(0)
         run.opt.step(run.g_ptrs)                     # uploads the gradient table outside the capture
@@ -733,7 +733,7 @@ def test_auto_schedule_settles_and_never_changes_results():
     cfg = small(tau=1, d=2, W=8, steps=90, params=custom_param_set([2**18, 4096 * 3 + 8, 1000]))
     outs = {}
     for sched in (pkg.SCHED_AUTO, pkg.SCHED_SERIAL, pkg.SCHED_OVERLAP):
-        run = GpuRun(cfg, schedule=sched)
+        run = DeviceRun(cfg, schedule=sched)
         if sched == pkg.SCHED_AUTO:
             assert run.opt.schedule_in_use()[:2] == (pkg.SCHED_AUTO, False)
         for _ in range(cfg.steps):
@@ -753,7 +753,7 @@ def test_head_start_of_the_side_stream_mean_never_changes_results():
     cfg = small(tau=2, d=1, W=8, steps=24, params=custom_param_set([2**18, 4096 * 3 + 8, 1000]))
     outs = []
     for us in (None, 0, 200):
-        run = GpuRun(cfg, schedule=pkg.SCHED_OVERLAP, side_threshold=0)
+        run = DeviceRun(cfg, schedule=pkg.SCHED_OVERLAP, side_threshold=0)
         if us is not None:
             run.opt.set_side_stream_head_start(us)
         for _ in range(cfg.steps):
@@ -768,7 +768,7 @@ def test_head_start_of_the_side_stream_mean_never_changes_results():
 def test_snapshot_auto_switches_to_stored_snapshots_after_its_budget():
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=4, xi=0.125, steps=160, params=custom_param_set(SETS["matrix"]))     # budget: 125 steps
-    run = GpuRun(cfg)
+    run = DeviceRun(cfg)
     run.opt.profile(1, 4096)
     for _ in range(cfg.steps):
         run.step()
@@ -792,7 +792,7 @@ def test_default_fusion_takes_the_one_kernel_step_only_where_it_changes_no_bit(t
     cfg = small(tau=tau, d=d, W=W, steps=4 * tau + 2 * d + 7, params=custom_param_set(SETS[pset]))
 
     def go(**kw):
-        run = GpuRun(cfg, layout=layout, **kw)
+        run = DeviceRun(cfg, layout=layout, **kw)
         run.opt.profile(1, 4096)
         for _ in range(cfg.steps):
             run.step()
@@ -811,7 +811,7 @@ def test_default_fusion_takes_the_one_kernel_step_only_where_it_changes_no_bit(t
     x, n = go(snapshot=pkg.SNAPSHOT_ZERO_COPY, schedule=pkg.SCHED_SERIAL)
     assert n["step_mean"] + n["step_mean_merge"] == 0, n
     odd = small(tau=tau, d=d, W=3, steps=cfg.steps, params=custom_param_set(SETS[pset]))
-    run = GpuRun(odd, layout=layout, snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_SERIAL)
+    run = DeviceRun(odd, layout=layout, snapshot=pkg.SNAPSHOT_COPY, schedule=pkg.SCHED_SERIAL)
     run.opt.profile(1, 4096)
     for _ in range(odd.steps):
         run.step()
@@ -829,7 +829,7 @@ def test_three_thousand_steps(mode, bound):
     import oracle
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=8, steps=3000, params=custom_param_set([4096 * 5 + 8, 1000, 64]))
-    run = GpuRun(cfg, snapshot=getattr(pkg, mode))
+    run = DeviceRun(cfg, snapshot=getattr(pkg, mode))
     ref = oracle.Oracle(cfg.W, cfg.P, cfg.d, cfg.tau, cfg.lr, cfg.momentum, cfg.wd, wl.init_weights(cfg).numpy(), xi=cfg.xi, dtype="f64")
     worst = 0.0
     for k in range(cfg.steps):
@@ -849,7 +849,7 @@ def test_smallest_xi_of_the_zero_copy_path_over_a_whole_config():
     import paper_2006_00441_amd as pkg
     cfg = wl.get_config("resnet50_w8").scaled(xi=0.125)
     idx = sample_indices(cfg)
-    run = GpuRun(cfg, layout="matrix", snapshot=pkg.SNAPSHOT_ZERO_COPY)
+    run = DeviceRun(cfg, layout="matrix", snapshot=pkg.SNAPSHOT_ZERO_COPY)
     run.opt.profile(1, 1000)
     for _ in range(cfg.steps):
         run.step()
@@ -920,7 +920,7 @@ def test_average_now(W, P, xi):
 def test_more_than_32_replicas(layout, pset, snapshot):
     import paper_2006_00441_amd as pkg
     cfg = small(tau=1, d=2, W=40, steps=11, params=custom_param_set(SETS[pset]))
-    run = GpuRun(cfg, layout=layout, snapshot=getattr(pkg, snapshot))
+    run = DeviceRun(cfg, layout=layout, snapshot=getattr(pkg, snapshot))
     assert run.opt.addressing() == pkg.ADDR_RECORDS
     for _ in range(cfg.steps):
         run.step()
